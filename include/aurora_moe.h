@@ -1,0 +1,206 @@
+/*
+ * aurora_moe.h - C ABI of the MI355X (gfx950) MoE-layer share library.
+ *
+ * One GPU's share of an expert-parallel MoE layer, in the order the paper's
+ * Sec. 2.1 lists the phases: Gate -> first all-to-all (only its buffer side is
+ * built: the send buffer, laid out in the transmission order planned by
+ * Sec. 4.2) -> expert FFN -> second all-to-all (only its layout contract) ->
+ * Aggregation; plus the two host-side planners of Sec. 4.2 / 5.2 (transmission
+ * order) and Sec. 6.2 (expert colocation by bottleneck matching).
+ *
+ * Conventions
+ *   - Every function returns MOE_OK (0) or a negative moe_status; nothing
+ *     throws, aborts or exits.  moe_last_error() gives a thread-local detail
+ *     string for the last failing call on the calling thread.
+ *   - "device" pointers are HIP device memory owned by the caller; "host"
+ *     pointers are ordinary host memory.  The library never frees or keeps a
+ *     caller's pointer beyond the call (device work is asynchronous on
+ *     `stream`, so device buffers must stay alive until that work is done).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Device entry points only enqueue work: no synchronisation, no
+ *     device-to-host copy.  The transmission order is planned offline from
+ *     historical statistics (Sec. 2.4), so it is an input, never waited for.
+ *   - Matrices are row-major.  A "slot" is a (token, choice) pair, id t*k + j.
+ *   - dtype: MOE_F32 (0) = IEEE fp32 storage; MOE_BF16 (1) = bfloat16 storage.
+ *     Accumulation is fp64 in the gate (indices must not depend on summation
+ *     order) and fp32 elsewhere.
+ *   - Arguments are validated before anything is launched: NULL where not
+ *     allowed / non-positive sizes -> MOE_EINVAL; inconsistent sizes (k > E,
+ *     limits exceeded, maps out of range, dest_order not a permutation)
+ *     -> MOE_ESHAPE; unknown dtype/act -> MOE_EDTYPE; row size not a multiple of
+ *     16 bytes or a pointer not 16-byte aligned -> MOE_EALIGN; a failing HIP call
+ *     -> MOE_EHIP (hipGetErrorString in moe_last_error()).
+ *   - Limits: E <= 256, G <= 64, k <= 16, T*k < 2^31.
+ */
+#ifndef AURORA_MOE_H
+#define AURORA_MOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MOE_OK = 0,
+    MOE_EINVAL = -1,
+    MOE_ESHAPE = -2,
+    MOE_EDTYPE = -3,
+    MOE_EALIGN = -4,
+    MOE_ENOMEM = -5,
+    MOE_EHIP = -6,
+    MOE_EINTERNAL = -7
+} moe_status;
+
+enum { MOE_F32 = 0, MOE_BF16 = 1 };
+enum { MOE_ACT_SILU_MLP = 0, MOE_ACT_GELU_MLP = 1, MOE_ACT_SWIGLU = 2 };
+
+/* Name of a status code; static storage. */
+const char* moe_status_str(int status);
+/* Detail of the last error on this thread; static thread-local storage, "" if none. */
+const char* moe_last_error(void);
+
+/* Shape of one GPU's share (notation of Sec. 4, Table 1, with n = G GPUs). */
+typedef struct {
+    int32_t T;        /* local tokens */
+    int32_t H;        /* hidden size */
+    int32_t E;        /* routed experts in the layer */
+    int32_t k;        /* experts per token ("one or two" in Sec. 2.1; any 1..16 here) */
+    int32_t G;        /* GPUs the experts are spread over */
+    int32_t dtype;    /* storage type of x, Wg, send/return buffers, y */
+    int32_t renorm;   /* 0: combine weight = softmax probability; 1: divided by the sum of the k chosen */
+    int32_t capacity; /* rows kept per expert on this source GPU; 0 = unlimited */
+} moe_shape;
+
+/* Opaque per-shape context.  Owns only small device scratch for the counting
+ * scans (a few KB per 1024 slots), allocated once in moe_ctx_create on the
+ * current device.  A context must not be used by two streams at once. */
+typedef struct moe_ctx moe_ctx;
+int moe_ctx_create(moe_ctx** out, const moe_shape* shape);
+int moe_ctx_destroy(moe_ctx* ctx); /* NULL is accepted */
+
+/* Gate (Sec. 2.1): logit[t,e] = sum_h x[t,h]*Wg[e,h] (+ gate_bias[e]); the k
+ * largest logits are chosen, listed by descending logit, equal logits resolved
+ * to the lower expert index; weight = softmax over all E logits at the chosen
+ * expert (divided by the sum of the k weights when renorm = 1).
+ *   x          device [T,H] dtype      Wg        device [E,H] dtype
+ *   gate_bias  device [E] fp32, may be NULL
+ *   topk_idx   device [T,k] int32 out  topk_w    device [T,k] fp32 out
+ * Logits are accumulated in fp64, so the indices equal those of an exact
+ * evaluation whenever the k-th and (k+1)-th logits differ by more than a few
+ * ulps of fp64. */
+int moe_route(moe_ctx* ctx, const void* x, const void* Wg, const float* gate_bias,
+              int32_t* topk_idx, float* topk_w, void* stream);
+
+/* Row g of the first all-to-all's traffic matrix D_N (Sec. 4: d_gj = tokens GPU
+ * g sends to GPU j), in slots, after the capacity rule: a slot is kept iff fewer
+ * than `capacity` slots with a smaller id chose the same expert.
+ *   topk_idx       device [T,k]      expert_to_gpu  HOST [E], values in [0,G)
+ *   expert_count   device [E] out: kept slots per expert
+ *   dest_count     device [G] out: kept slots per destination GPU (self included)
+ *   n_dropped      device [1] out */
+int moe_traffic(moe_ctx* ctx, const int32_t* topk_idx, const int32_t* expert_to_gpu,
+                int32_t* expert_count, int32_t* dest_count, int32_t* n_dropped, void* stream);
+
+/* Buffer layer in the planned transmission order (Sec. 3, "Communication
+ * scheduling"): kept slots are copied into the send buffer destination by
+ * destination in `dest_order`; inside a destination expert by expert (ascending
+ * id); inside an expert by ascending slot id.
+ *   x            device [T,H] dtype     topk_idx  device [T,k]
+ *   expert_to_gpu HOST [E]              dest_order HOST [G], a permutation of 0..G-1
+ *   send_buf     device [T*k,H] dtype out (rows beyond the kept count untouched)
+ *   slot_to_row  device [T*k] out, -1 for a dropped slot
+ *   row_to_slot  device [T*k] out (entries beyond the kept count untouched)
+ *   seg_offset   device [E+1] out: first row of each (destination, expert) segment in send order
+ *   seg_expert   device [E] out: expert id of each segment */
+int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* topk_idx, const int32_t* expert_to_gpu,
+                 const int32_t* dest_order, void* send_buf, int32_t* slot_to_row,
+                 int32_t* row_to_slot, int32_t* seg_offset, int32_t* seg_expert, void* stream);
+
+/* One expert's weights, stored [out,in] row-major in `dtype`, device memory. */
+typedef struct {
+    const void* w1;     /* [F,H]: the only up-projection (MLP) or the gate projection (SwiGLU) */
+    const void* w_up;   /* [F,H] for SwiGLU, NULL otherwise */
+    const void* w_down; /* [H,F] */
+} moe_expert_w;
+
+/* Bytes of device workspace moe_expert_ffn needs for up to R_max rows (the
+ * [R,F] intermediate plus a tile map); 0 if an argument is invalid. */
+size_t moe_ffn_workspace_bytes(int32_t R_max, int32_t H, int32_t F, int32_t act, int32_t dtype);
+
+/* Expert FFN (Sec. 2.1) over the rows this GPU received: rows
+ * [seg_offset[i], seg_offset[i+1]) go through local expert seg_expert[i].
+ * Input and output rows have the same size (Sec. 2.2), so `out` mirrors `recv`.
+ *   act 0: Wd.silu(W1.x)   1: Wd.gelu_tanh(W1.x)   2: Wd.(silu(W1.x) * (Wu.x))
+ *   recv        device [R,H] dtype       R  rows in recv/out (>= seg_offset[nseg])
+ *   seg_offset  device [nseg+1] int32, non-decreasing, seg_offset[0] >= 0
+ *   seg_expert  device [nseg] int32 in [0,n_local)
+ *   experts     HOST [n_local], n_local <= 64
+ *   out         device [R,H] dtype; rows outside every segment are left untouched
+ *   workspace   device, >= moe_ffn_workspace_bytes(R,H,F,act,dtype), 256-byte aligned
+ * bf16: H and F must be multiples of 128; the [R,F] intermediate is rounded to
+ * bf16 once.  fp32: any sizes with H, F multiples of 4. */
+int moe_expert_ffn(const void* recv, int32_t R, const int32_t* seg_offset, const int32_t* seg_expert,
+                   int32_t nseg, const moe_expert_w* experts, int32_t n_local, int32_t H, int32_t F,
+                   int32_t act, int32_t dtype, void* out, void* workspace, size_t workspace_bytes,
+                   void* stream);
+
+/* Aggregation (Sec. 2.1): y[t] = sum_j topk_w[t,j] * ret[slot_to_row[t*k+j]] over
+ * kept slots (+ shared_out[t]).  `ret` is in send-buffer row order: the second
+ * all-to-all reverses the first with equal sizes (Sec. 2.2).
+ *   ret         device [T*k,H] dtype     slot_to_row device [T*k]
+ *   topk_w      device [T,k] fp32        shared_out  device [T,H] dtype or NULL
+ *   y           device [T,H] dtype out (fp32 accumulation, rounded once) */
+int moe_combine(moe_ctx* ctx, const void* ret, const int32_t* slot_to_row, const float* topk_w,
+                const void* shared_out, void* y, void* stream);
+
+/* ------------------------------------------------------------------ host planners */
+
+/* Result of aurora_order; arrays are owned by the library until
+ * aurora_schedule_free (which also zeroes the struct). */
+typedef struct {
+    int32_t n;
+    int32_t n_rounds;
+    double* duration;        /* [n_rounds] length of each round */
+    int32_t* dst;            /* [n_rounds*n] receiver of GPU i in round r, -1 = idle */
+    int32_t* dest_order;     /* [n*n] row i: the order in which GPU i sends to all n destinations
+                                (real flows by planned start, then empty ones, then i itself) */
+    double* start;           /* [n*n] planned start of flow i->j in the per-destination order, -1 if empty */
+    double bmax;             /* Theorem 2 / Theorem 4 lower bound */
+    double port_bound;       /* looser bound max(sum_j d_ij/B_i, sum_i d_ij/B_j) */
+    double makespan_rounds;  /* sum of round durations (== bmax up to rounding) */
+    double makespan_order;   /* end of the last flow in the per-destination plan */
+} aurora_schedule;
+
+/* Transmission order of one all-to-all (Sec. 4.2 Theorem 2 and Algorithm 1;
+ * Sec. 5.2 Theorem 4 / Appendix B for per-GPU rates).
+ *   n   GPUs (1..64)      D  HOST [n*n] tokens i->j, diagonal ignored, entries >= 0
+ *   B   HOST [n] link rates > 0, or NULL for all 1
+ * Traffic is scaled to p_ij = d_ij / min(B_i,B_j).  `rounds` is the schedule of
+ * Appendix A: the padded matrix is decomposed into permutations, in each round
+ * every GPU sends to a distinct GPU; it attains bmax.  `dest_order` is a
+ * non-preemptive per-destination order from a greedy reading of Algorithm 1
+ * (bottleneck GPU first, then GPUs by remaining traffic, each flow placed in the
+ * earliest gap free at both ends). */
+int aurora_order(int32_t n, const int64_t* D, const double* B, aurora_schedule* out);
+void aurora_schedule_free(aurora_schedule* s);
+
+/* Completion time of the all-to-all on the big-switch model (Sec. 2.4) when GPU
+ * i sends to order[i*n .. i*n+n) one destination after another; a receiver with
+ * m incoming flows gives each B_recv/m, a flow runs at min(B_send, share). */
+int aurora_simulate(int32_t n, const int64_t* D, const double* B, const int32_t* order, double* time_out);
+
+/* Expert colocation of two models (Sec. 6.2, Case II): edge weight
+ * max(a_i + b_j, a_{n+i} + b_{n+j}) from the off-diagonal row (send) and column
+ * (receive) sums of Da and Db; minimise the largest weight over matchings that
+ * give every expert of a (na <= nb) a distinct expert of b.  Binary search over
+ * the sorted weights with Hopcroft-Karp as the feasibility test.
+ *   Da HOST [na*na], Db HOST [nb*nb], entries >= 0;  pair HOST [na] out;  bottleneck HOST [1] out */
+int colocate_match(int32_t na, int32_t nb, const int64_t* Da, const int64_t* Db, int32_t* pair,
+                   double* bottleneck);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AURORA_MOE_H */

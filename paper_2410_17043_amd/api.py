@@ -1,0 +1,175 @@
+"""Thin Python binding of the C ABI: argument marshalling only.
+
+Device entry points take torch tensors that already live on the GPU (torch is used
+for device memory and streams, nothing else) and enqueue work on torch's current
+stream.  Every step of the path runs in the library's own kernels.
+"""
+from __future__ import annotations
+
+import ctypes as C
+
+import numpy as np
+import torch
+
+from . import _lib
+from ._lib import moe_shape, moe_expert_w, aurora_schedule
+
+F32, BF16 = 0, 1
+ACT_SILU_MLP, ACT_GELU_MLP, ACT_SWIGLU = 0, 1, 2
+_DT = {torch.float32: F32, torch.bfloat16: BF16, "fp32": F32, "bf16": BF16}
+TORCH_DTYPE = {F32: torch.float32, BF16: torch.bfloat16, "fp32": torch.float32, "bf16": torch.bfloat16}
+
+
+class MoeError(RuntimeError):
+    def __init__(self, fn, status):
+        lib = _lib.load()
+        self.status = status
+        self.name = lib.moe_status_str(status).decode()
+        super().__init__("%s failed: %s (%s)" % (fn, self.name, lib.moe_last_error().decode()))
+
+
+def _check(fn, rc):
+    if rc != 0:
+        raise MoeError(fn, rc)
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("device entry points need contiguous GPU tensors")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _i32_array(values):
+    a = np.ascontiguousarray(values, dtype=np.int32)
+    return a, a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+class MoeCtx:
+    """Owner of a moe_ctx (small scan scratch on the current device)."""
+
+    def __init__(self, T, H, E, k, G, dtype, renorm=0, capacity=0):
+        self.lib = _lib.load()
+        self.shape = moe_shape(T, H, E, k, G, _DT[dtype], renorm, capacity)
+        self.handle = C.c_void_p()
+        _check("moe_ctx_create", self.lib.moe_ctx_create(C.byref(self.handle), C.byref(self.shape)))
+
+    def close(self):
+        if self.handle:
+            self.lib.moe_ctx_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def moe_route(ctx, x, w_gate, gate_bias, topk_idx, topk_w):
+    _check("moe_route", ctx.lib.moe_route(ctx.handle, _ptr(x), _ptr(w_gate), _ptr(gate_bias), _ptr(topk_idx),
+                                          _ptr(topk_w), _stream()))
+
+
+def moe_traffic(ctx, topk_idx, expert_to_gpu, expert_count, dest_count, n_dropped):
+    _, e2g = _i32_array(expert_to_gpu)
+    _check("moe_traffic", ctx.lib.moe_traffic(ctx.handle, _ptr(topk_idx), e2g, _ptr(expert_count), _ptr(dest_count),
+                                              _ptr(n_dropped), _stream()))
+
+
+def moe_dispatch(ctx, x, topk_idx, expert_to_gpu, dest_order, send_buf, slot_to_row, row_to_slot, seg_offset,
+                 seg_expert):
+    _a, e2g = _i32_array(expert_to_gpu)
+    _b, order = _i32_array(dest_order)
+    _check("moe_dispatch", ctx.lib.moe_dispatch(ctx.handle, _ptr(x), _ptr(topk_idx), e2g, order, _ptr(send_buf),
+                                                _ptr(slot_to_row), _ptr(row_to_slot), _ptr(seg_offset),
+                                                _ptr(seg_expert), _stream()))
+
+
+def moe_ffn_workspace_bytes(R_max, H, F, act, dtype):
+    return int(_lib.load().moe_ffn_workspace_bytes(R_max, H, F, act, _DT[dtype]))
+
+
+def expert_table(experts):
+    """HOST array of moe_expert_w from a list of dicts of device tensors (w1, w_up or None, w_down)."""
+    arr = (moe_expert_w * len(experts))()
+    for i, w in enumerate(experts):
+        arr[i].w1 = w["w1"].data_ptr()
+        arr[i].w_up = w["w_up"].data_ptr() if w.get("w_up") is not None else None
+        arr[i].w_down = w["w_down"].data_ptr()
+    return arr
+
+
+def moe_expert_ffn(recv, R, seg_offset, seg_expert, nseg, experts, H, F, act, dtype, out, workspace):
+    """`experts` is either a list of weight dicts or a table made by expert_table()."""
+    tab = experts if isinstance(experts, C.Array) else expert_table(experts)
+    _check("moe_expert_ffn", _lib.load().moe_expert_ffn(
+        _ptr(recv), R, _ptr(seg_offset), _ptr(seg_expert), nseg, tab, len(tab), H, F, act, _DT[dtype], _ptr(out),
+        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
+
+
+def moe_combine(ctx, ret, slot_to_row, topk_w, shared_out, y):
+    _check("moe_combine", ctx.lib.moe_combine(ctx.handle, _ptr(ret), _ptr(slot_to_row), _ptr(topk_w),
+                                              _ptr(shared_out), _ptr(y), _stream()))
+
+
+# ------------------------------------------------------------------ host planners (no GPU needed)
+def _i64_matrix(D):
+    a = np.ascontiguousarray(D, dtype=np.int64)
+    return a, a.ctypes.data_as(C.POINTER(C.c_int64))
+
+
+def _f64_array(B):
+    if B is None:
+        return None, None
+    a = np.ascontiguousarray(B, dtype=np.float64)
+    return a, a.ctypes.data_as(C.POINTER(C.c_double))
+
+
+def aurora_order(D, B=None):
+    """Plan one all-to-all; returns a dict of numpy arrays and scalars (the C struct is freed here)."""
+    lib = _lib.load()
+    Dm, Dp = _i64_matrix(D)
+    n = Dm.shape[0]
+    _Bm, Bp = _f64_array(B)
+    s = aurora_schedule()
+    _check("aurora_order", lib.aurora_order(n, Dp, Bp, C.byref(s)))
+    try:
+        nr = s.n_rounds
+        out = {
+            "n": n, "n_rounds": nr,
+            "duration": np.array([s.duration[r] for r in range(nr)], dtype=np.float64),
+            "dst": np.array([s.dst[i] for i in range(nr * n)], dtype=np.int32).reshape(nr, n),
+            "dest_order": np.array([s.dest_order[i] for i in range(n * n)], dtype=np.int32).reshape(n, n),
+            "start": np.array([s.start[i] for i in range(n * n)], dtype=np.float64).reshape(n, n),
+            "bmax": s.bmax, "port_bound": s.port_bound, "makespan_rounds": s.makespan_rounds,
+            "makespan_order": s.makespan_order,
+        }
+    finally:
+        lib.aurora_schedule_free(C.byref(s))
+    return out
+
+
+def aurora_simulate(D, B, order):
+    lib = _lib.load()
+    Dm, Dp = _i64_matrix(D)
+    _Bm, Bp = _f64_array(B)
+    _o, op = _i32_array(order)
+    t = C.c_double()
+    _check("aurora_simulate", lib.aurora_simulate(Dm.shape[0], Dp, Bp, op, C.byref(t)))
+    return t.value
+
+
+def colocate_match(Da, Db):
+    lib = _lib.load()
+    A, Ap = _i64_matrix(Da)
+    Bm, Bp = _i64_matrix(Db)
+    pair = (C.c_int32 * A.shape[0])()
+    bott = C.c_double()
+    _check("colocate_match", lib.colocate_match(A.shape[0], Bm.shape[0], Ap, Bp, pair, C.byref(bott)))
+    return list(pair), bott.value

@@ -1,0 +1,425 @@
+// Expert FFN of Sec. 2.1 over the rows a GPU received: a ragged grouped GEMM pair.
+//
+//   GEMM1  Hmid[R,F] = act(recv . W1^T)            (SwiGLU: silu(recv . W1^T) * (recv . Wu^T))
+//   GEMM2  out[R,H]  = Hmid . Wd^T
+//
+// Both operands of both GEMMs are K-contiguous ([rows,K] activations, [out,in]
+// weights), which is exactly the operand layout of the CDNA MFMA instructions.
+// Rows are grouped in segments, one local expert per segment; a small device kernel
+// turns the segment list into a list of M-tiles (adjacent segments of the same
+// expert are merged, tiles never straddle experts), so nothing waits for the host.
+//
+// bf16 path: 256x256x64 block tile, 4 waves in 2x2, each wave 128x128 = 4x4 tiles of
+// v_mfma_f32_32x32x16_bf16, fp32 accumulators; operands staged through LDS with an
+// XOR swizzle of the 16-byte k-chunks (conflict-free ds_read_b128); the next k-tile
+// is fetched into registers while the current one is multiplied.  For SwiGLU the B
+// tile holds 128 gate rows and 128 up rows arranged so that a wave owns the gate and
+// the up product of the same 64 columns: the activation is applied on registers and
+// the intermediate is written once, in bf16.  Block ids are remapped so that the
+// blocks that share an XCD's L2 work on neighbouring tiles.
+//
+// fp32 path (correctness configuration): plain 64x64x16 LDS-tiled vector-ALU GEMM.
+#include "common.h"
+
+namespace {
+
+constexpr int kMaxSeg = 1024;
+
+struct TileMap {
+    int32_t* n_tiles;   // [1]
+    int32_t* row0;      // [max_tiles] first row of the tile
+    int32_t* nrows;     // [max_tiles] valid rows (1..BM)
+    int32_t* expert;    // [max_tiles] local expert
+};
+
+struct ExpertTable {
+    const void* w1[MOE_MAX_LOCAL];
+    const void* w_up[MOE_MAX_LOCAL];
+    const void* w_down[MOE_MAX_LOCAL];
+};
+
+__host__ __device__ inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+inline int max_tiles_for(int R) { return R / 64 + 1 + kMaxSeg; }
+inline size_t tilemap_bytes(int R) { return align256(256 + 3 * sizeof(int32_t) * (size_t)max_tiles_for(R)); }
+
+TileMap tilemap_at(void* ws, int R) {
+    TileMap m;
+    char* p = reinterpret_cast<char*>(ws);
+    m.n_tiles = reinterpret_cast<int32_t*>(p);
+    m.row0 = reinterpret_cast<int32_t*>(p + 256);
+    m.nrows = m.row0 + max_tiles_for(R);
+    m.expert = m.nrows + max_tiles_for(R);
+    return m;
+}
+
+// One block.  Thread 0 merges adjacent segments of the same expert into runs; all
+// threads then cut the runs into tiles of BM rows.
+__global__ __launch_bounds__(256) void tilemap_kernel(const int32_t* __restrict__ seg_offset,
+                                                      const int32_t* __restrict__ seg_expert, int nseg, int R, int BM,
+                                                      int n_local, TileMap m) {
+    __shared__ int run_lo[kMaxSeg], run_hi[kMaxSeg], run_exp[kMaxSeg], run_tile0[kMaxSeg];
+    __shared__ int n_runs, n_tiles;
+    if (threadIdx.x == 0) {
+        int nr = 0, nt = 0, i = 0;
+        while (i < nseg) {
+            const int e = seg_expert[i];
+            int lo = seg_offset[i], hi = seg_offset[i + 1];
+            int j = i + 1;
+            while (j < nseg && seg_expert[j] == e) { hi = seg_offset[j + 1]; ++j; }
+            i = j;
+            lo = max(lo, 0);
+            hi = min(hi, R);
+            if (hi > lo && e >= 0 && e < n_local) {
+                run_lo[nr] = lo; run_hi[nr] = hi; run_exp[nr] = e; run_tile0[nr] = nt;
+                nt += (hi - lo + BM - 1) / BM;
+                ++nr;
+            }
+        }
+        n_runs = nr;
+        n_tiles = nt;
+        *m.n_tiles = nt;
+    }
+    __syncthreads();
+    for (int r = 0; r < n_runs; ++r) {
+        const int lo = run_lo[r], hi = run_hi[r];
+        const int cnt = (hi - lo + BM - 1) / BM;
+        for (int t = threadIdx.x; t < cnt; t += 256) {
+            const int id = run_tile0[r] + t;
+            m.row0[id] = lo + t * BM;
+            m.nrows[id] = min(BM, hi - (lo + t * BM));
+            m.expert[id] = run_exp[r];
+        }
+    }
+}
+
+enum { EPI_PLAIN = 0, EPI_SILU = 1, EPI_GELU = 2, EPI_SWIGLU = 3 };
+
+__device__ __forceinline__ float silu_f(float a) { return a / (1.f + __expf(-a)); }
+__device__ __forceinline__ float gelu_tanh_f(float a) {
+    const float u = 0.7978845608028654f * (a + 0.044715f * a * a * a);
+    return 0.5f * a * (1.f + tanhf(u));
+}
+template <int EPI> __device__ __forceinline__ float epilogue(float a, float b) {
+    if (EPI == EPI_SILU) return silu_f(a);
+    if (EPI == EPI_GELU) return gelu_tanh_f(a);
+    if (EPI == EPI_SWIGLU) return silu_f(a) * b;
+    return a;
+}
+
+// Remap the linear block id so that (1) the blocks resident on one XCD (ids equal
+// mod 8) get consecutive virtual ids and (2) consecutive virtual ids walk GROUP_M
+// M-tiles before moving to the next N-tile, so an XCD's L2 holds few distinct tiles.
+__device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m, int tiles_n, int* tm, int* tn) {
+    constexpr int GROUP_M = 8;
+    int vid = bid;
+    if (nblocks % 8 == 0) vid = (bid % 8) * (nblocks / 8) + bid / 8;
+    const int per_group = GROUP_M * tiles_n;
+    const int g = vid / per_group;
+    const int first_m = g * GROUP_M;
+    const int gsz = min(tiles_m - first_m, GROUP_M);
+    const int in_g = vid - g * per_group;
+    *tm = first_m + in_g % gsz;
+    *tn = in_g / gsz;
+}
+
+// ------------------------------------------------------------------------------------ fp32
+// C[r, n] = epi( sum_k A[r,k] * B0[n,k], sum_k A[r,k] * B1[n,k] ), 64x64 tile, 4x4 per thread.
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ A, int lda, TileMap m,
+                                                       ExpertTable tab, int which0, int which1, int N, int K,
+                                                       float* __restrict__ C, int ldc, int tiles_n) {
+    __shared__ float As[16][65], B0s[16][65], B1s[(EPI == EPI_SWIGLU) ? 16 : 1][65];
+    const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x % tiles_n;
+    if (tile_m >= *m.n_tiles) return;
+    const int row0 = m.row0[tile_m], nrows = m.nrows[tile_m], ex = m.expert[tile_m];
+    auto pick = [&](int which) -> const float* {
+        return reinterpret_cast<const float*>(which == 0 ? tab.w1[ex] : which == 1 ? tab.w_up[ex] : tab.w_down[ex]);
+    };
+    const float* B0 = pick(which0);
+    const float* B1 = (EPI == EPI_SWIGLU) ? pick(which1) : nullptr;
+    const int n0 = tile_n * 64;
+    const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
+    float acc0[4][4] = {}, acc1[4][4] = {};
+    for (int k0 = 0; k0 < K; k0 += 16) {
+        for (int q = threadIdx.x; q < 64 * 16; q += 256) {
+            const int r = q / 16, kk = q % 16;
+            const int gr = row0 + min(r, nrows - 1);
+            As[kk][r] = (k0 + kk < K) ? A[(size_t)gr * lda + k0 + kk] : 0.f;
+            const int gn = n0 + r;
+            const bool ok = gn < N && k0 + kk < K;
+            B0s[kk][r] = ok ? B0[(size_t)gn * K + k0 + kk] : 0.f;
+            if (EPI == EPI_SWIGLU) B1s[kk][r] = ok ? B1[(size_t)gn * K + k0 + kk] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            float a[4], b0[4], b1[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; b0[i] = B0s[kk][tx * 4 + i]; }
+            if (EPI == EPI_SWIGLU)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) b1[i] = B1s[kk][tx * 4 + i];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    acc0[i][j] = fmaf(a[i], b0[j], acc0[i][j]);
+                    if (EPI == EPI_SWIGLU) acc1[i][j] = fmaf(a[i], b1[j], acc1[i][j]);
+                }
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = ty * 4 + i;
+        if (r >= nrows) continue;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = n0 + tx * 4 + j;
+            if (n < N) C[(size_t)(row0 + r) * ldc + n] = epilogue<EPI>(acc0[i][j], acc1[i][j]);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------ bf16 MFMA
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 256, BN = 256, BK = 32, STAGES = 4;
+constexpr int kTileBytes = BM * BK * 2;        // one 256 x 32 bf16 operand tile: 16 KB
+constexpr int kStageBytes = 2 * kTileBytes;    // A tile then B tile
+constexpr int kLdsBytes = STAGES * kStageBytes;
+
+// An operand tile is stored as 16 blocks of 16 rows; a block is 1 KB = 64 slots of
+// 16 bytes and is filled by ONE wave-wide direct-to-LDS load (lane l fills slot l).
+// Inside a block, 16-byte chunk c (0..3) of row r (0..15) sits in slot
+//     (r/2)*8 + (((r%2)*4 + c) ^ (r/2))
+// so that the 8 lanes served together by a ds_read_b128 (8 consecutive rows, same
+// chunk) touch 8 different 16-byte bank groups.
+__device__ __forceinline__ int slot_of(int r, int c) { return ((r >> 1) << 3) + ((((r & 1) << 2) + c) ^ (r >> 1)); }
+// inverse for the loading lane: which (row, chunk) of the block lane l must fetch
+__device__ __forceinline__ void rc_of_slot(int l, int* r, int* c) {
+    const int rp = l >> 3, v = (l & 7) ^ rp;
+    *r = rp * 2 + (v >> 2);
+    *c = v & 3;
+}
+// byte offset of (row, chunk) inside a 256-row tile
+__device__ __forceinline__ int tile_off(int row, int c) { return ((row >> 4) << 10) + (slot_of(row & 15, c) << 4); }
+
+// SwiGLU tile row r (0..255) -> (matrix, column): wave-column wn = r / 128 owns 64 output
+// columns; its first 64 tile rows are W1 rows, the next 64 the Wu rows of the same columns.
+template <int EPI>
+__global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __restrict__ A, int lda, TileMap m,
+                                                           ExpertTable tab, int which0, int which1, int N, int K,
+                                                           uint16_t* __restrict__ C, int ldc, int tiles_n,
+                                                           int max_tiles_m) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    constexpr int NOUT = (EPI == EPI_SWIGLU) ? 128 : 256;                  // output columns per block
+    const int n_tiles_m = *m.n_tiles;
+    int tile_m, tile_n;
+    tile_of_block(blockIdx.x, gridDim.x, max_tiles_m, tiles_n, &tile_m, &tile_n);
+    if (tile_m >= n_tiles_m) return;
+    const int row0 = m.row0[tile_m], nrows = m.nrows[tile_m], ex = m.expert[tile_m];
+    auto pick = [&](int which) -> const uint16_t* {
+        return reinterpret_cast<const uint16_t*>(which == 0 ? tab.w1[ex] : which == 1 ? tab.w_up[ex] : tab.w_down[ex]);
+    };
+    const uint16_t* B0 = pick(which0);
+    const uint16_t* B1 = (EPI == EPI_SWIGLU) ? pick(which1) : B0;
+    const int n0 = tile_n * NOUT;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // Direct-to-LDS staging.  A stage is 32 blocks of 1 KB (16 of A, 16 of B); wave w
+    // fills blocks w, w+4, ...: 4 of A and 4 of B per stage.
+    int lr, lc;
+    rc_of_slot(lane, &lr, &lc);
+    const uint16_t* a_src[4];
+    const uint16_t* b_src[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r = (wave + 4 * i) * 16 + lr;              // tile row this lane fetches
+        a_src[i] = A + (size_t)(row0 + min(r, nrows - 1)) * lda + lc * 8;
+        int col;
+        const uint16_t* Bm;
+        if (EPI == EPI_SWIGLU) {
+            const int w = r >> 7, sub = r & 127;
+            Bm = (sub < 64) ? B0 : B1;
+            col = n0 + w * 64 + (sub & 63);
+        } else {
+            Bm = B0;
+            col = n0 + r;
+        }
+        b_src[i] = Bm + (size_t)min(col, N - 1) * K + lc * 8;
+    }
+    auto issue = [&](int kt, int buf) {
+        unsigned char* sa = lds + buf * kStageBytes;
+        unsigned char* sb = sa + kTileBytes;
+        const int k0 = kt * BK;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            __builtin_amdgcn_global_load_lds(a_src[i] + k0, (__attribute__((address_space(3))) void*)(sa + (wave + 4 * i) * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(b_src[i] + k0, (__attribute__((address_space(3))) void*)(sb + (wave + 4 * i) * 1024), 16, 0, 0);
+        }
+    };
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    const int nk = K / BK;
+#pragma unroll
+    for (int p = 0; p < STAGES - 1; ++p) issue(min(p, nk - 1), p);
+
+    const int fr = lane & 31, fk = lane >> 5;      // fragment row within a 32-row tile, which k-half
+    int a_off[4][2], b_off[4][2];                  // byte offsets inside a stage, per 32-row tile and k-step
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            a_off[i][s] = tile_off(wm * 128 + i * 32 + fr, 2 * s + fk);
+            b_off[i][s] = kTileBytes + tile_off(wn * 128 + i * 32 + fr, 2 * s + fk);
+        }
+
+    for (int kt = 0; kt < nk; ++kt) {
+        // tile kt has landed once at most the 2 younger tiles (8 loads each per wave) are outstanding
+        // (a bare barrier: __syncthreads() would add a fence that waits for ALL outstanding loads)
+        __builtin_amdgcn_s_waitcnt(0x4F70);        // vmcnt(16)
+        __builtin_amdgcn_s_barrier();
+        issue(min(kt + STAGES - 1, nk - 1), (kt + STAGES - 1) % STAGES);
+        const unsigned char* st = lds + (kt % STAGES) * kStageBytes;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {
+            bf16x8 af[4], bfr[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const bf16x8*>(st + a_off[i][s]);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(st + b_off[j][s]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): no load may still target LDS when the block ends
+
+    // epilogue: acc[i][j][e] is row (e/4)*8 + (lane/32)*4 + e%4, column lane%32 of tile (i, j)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int r = wm * 128 + i * 32 + (e >> 2) * 8 + fk * 4 + (e & 3);
+            if (r >= nrows) continue;
+            uint16_t* crow = C + (size_t)(row0 + r) * ldc;
+            if (EPI == EPI_SWIGLU) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const int col = n0 + wn * 64 + j * 32 + fr;
+                    if (col < N) crow[col] = (uint16_t)f32_to_bf16_bits(epilogue<EPI>(acc[i][j][e], acc[i][j + 2][e]));
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int col = n0 + wn * 128 + j * 32 + fr;
+                    if (col < N) crow[col] = (uint16_t)f32_to_bf16_bits(epilogue<EPI>(acc[i][j][e], 0.f));
+                }
+            }
+        }
+    }
+}
+
+template <int EPI>
+int launch_bf16(const void* A, int lda, const TileMap& m, const ExpertTable& tab, int which0, int which1, int N, int K,
+                void* C, int ldc, int R, int nseg, hipStream_t st) {
+    const int nout = (EPI == EPI_SWIGLU) ? 128 : 256;
+    const int tiles_n = (N + nout - 1) / nout;
+    const int max_tiles_m = (R + BM - 1) / BM + nseg;
+    const size_t lds = (size_t)kLdsBytes;
+    static bool attr_done = false;
+    if (!attr_done) {
+        MOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<EPI>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        attr_done = true;
+    }
+    hipLaunchKernelGGL((gemm_bf16_kernel<EPI>), dim3(max_tiles_m * tiles_n), dim3(256), lds, st,
+                       reinterpret_cast<const uint16_t*>(A), lda, m, tab, which0, which1, N, K,
+                       reinterpret_cast<uint16_t*>(C), ldc, tiles_n, max_tiles_m);
+    MOE_LAUNCH_CHECK("gemm_bf16_kernel");
+    return MOE_OK;
+}
+
+template <int EPI>
+int launch_f32(const void* A, int lda, const TileMap& m, const ExpertTable& tab, int which0, int which1, int N, int K,
+               void* C, int ldc, int R, int nseg, hipStream_t st) {
+    const int tiles_n = (N + 63) / 64;
+    const int max_tiles_m = (R + 63) / 64 + nseg;
+    hipLaunchKernelGGL((gemm_f32_kernel<EPI>), dim3(max_tiles_m * tiles_n), dim3(256), 0, st,
+                       reinterpret_cast<const float*>(A), lda, m, tab, which0, which1, N, K,
+                       reinterpret_cast<float*>(C), ldc, tiles_n);
+    MOE_LAUNCH_CHECK("gemm_f32_kernel");
+    return MOE_OK;
+}
+
+}  // namespace
+
+extern "C" size_t moe_ffn_workspace_bytes(int32_t R_max, int32_t H, int32_t F, int32_t act, int32_t dtype) {
+    if (R_max < 0 || H <= 0 || F <= 0 || act < 0 || act > 2 || (dtype != MOE_F32 && dtype != MOE_BF16)) return 0;
+    return tilemap_bytes(R_max) + align256((size_t)R_max * F * elem_size(dtype)) + 256;
+}
+
+extern "C" int moe_expert_ffn(const void* recv, int32_t R, const int32_t* seg_offset, const int32_t* seg_expert,
+                              int32_t nseg, const moe_expert_w* experts, int32_t n_local, int32_t H, int32_t F,
+                              int32_t act, int32_t dtype, void* out, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+    if (!recv || !seg_offset || !seg_expert || !experts || !out || !workspace)
+        return moe_set_error(MOE_EINVAL, "moe_expert_ffn: NULL argument");
+    if (R < 0 || nseg < 0 || H <= 0 || F <= 0) return moe_set_error(MOE_EINVAL, "moe_expert_ffn: negative size");
+    if (dtype != MOE_F32 && dtype != MOE_BF16) return moe_set_error(MOE_EDTYPE, "moe_expert_ffn: unknown dtype %d", dtype);
+    if (act < 0 || act > 2) return moe_set_error(MOE_EDTYPE, "moe_expert_ffn: unknown act %d", act);
+    if (n_local < 1 || n_local > MOE_MAX_LOCAL || nseg > kMaxSeg)
+        return moe_set_error(MOE_ESHAPE, "moe_expert_ffn: need 1 <= n_local <= %d and nseg <= %d", MOE_MAX_LOCAL, kMaxSeg);
+    if (dtype == MOE_BF16 && (H % 128 != 0 || F % 128 != 0))
+        return moe_set_error(MOE_ESHAPE, "moe_expert_ffn: bf16 needs H and F to be multiples of 128");
+    if (dtype == MOE_F32 && (H % 4 != 0 || F % 4 != 0))
+        return moe_set_error(MOE_EALIGN, "moe_expert_ffn: fp32 needs H and F to be multiples of 4");
+    if (!aligned16(recv) || !aligned16(out) || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+        return moe_set_error(MOE_EALIGN, "moe_expert_ffn: recv/out need 16-byte, workspace 256-byte alignment");
+    if (workspace_bytes < moe_ffn_workspace_bytes(R, H, F, act, dtype))
+        return moe_set_error(MOE_ESHAPE, "moe_expert_ffn: workspace too small (%zu < %zu)", workspace_bytes,
+                             moe_ffn_workspace_bytes(R, H, F, act, dtype));
+    ExpertTable tab;
+    for (int e = 0; e < n_local; ++e) {
+        if (!experts[e].w1 || !experts[e].w_down || (act == MOE_ACT_SWIGLU && !experts[e].w_up))
+            return moe_set_error(MOE_EINVAL, "moe_expert_ffn: expert %d has a NULL weight", e);
+        if (!aligned16(experts[e].w1) || !aligned16(experts[e].w_down) || !aligned16(experts[e].w_up))
+            return moe_set_error(MOE_EALIGN, "moe_expert_ffn: expert %d weights must be 16-byte aligned", e);
+        tab.w1[e] = experts[e].w1;
+        tab.w_up[e] = experts[e].w_up;
+        tab.w_down[e] = experts[e].w_down;
+    }
+    if (R == 0 || nseg == 0) return MOE_OK;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    TileMap m = tilemap_at(workspace, R);
+    void* hmid = reinterpret_cast<char*>(workspace) + tilemap_bytes(R);
+    const int bm = (dtype == MOE_BF16) ? BM : 64;
+    hipLaunchKernelGGL(tilemap_kernel, dim3(1), dim3(256), 0, st, seg_offset, seg_expert, nseg, R, bm, n_local, m);
+    MOE_LAUNCH_CHECK("tilemap_kernel");
+    int rc;
+    if (dtype == MOE_BF16) {
+        if (act == MOE_ACT_SWIGLU) rc = launch_bf16<EPI_SWIGLU>(recv, H, m, tab, 0, 1, F, H, hmid, F, R, nseg, st);
+        else if (act == MOE_ACT_GELU_MLP) rc = launch_bf16<EPI_GELU>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, st);
+        else rc = launch_bf16<EPI_SILU>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, st);
+        if (rc != MOE_OK) return rc;
+        return launch_bf16<EPI_PLAIN>(hmid, F, m, tab, 2, 2, H, F, out, H, R, nseg, st);
+    }
+    if (act == MOE_ACT_SWIGLU) rc = launch_f32<EPI_SWIGLU>(recv, H, m, tab, 0, 1, F, H, hmid, F, R, nseg, st);
+    else if (act == MOE_ACT_GELU_MLP) rc = launch_f32<EPI_GELU>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, st);
+    else rc = launch_f32<EPI_SILU>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, st);
+    if (rc != MOE_OK) return rc;
+    return launch_f32<EPI_PLAIN>(hmid, F, m, tab, 2, 2, H, F, out, H, R, nseg, st);
+}

@@ -1,0 +1,147 @@
+"""Host planners of the library against the oracle (CPU only)."""
+import itertools
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import paper_2410_17043_amd as P
+import workloads as W
+from oracle import matching as OM
+from oracle import schedule as OS
+
+
+def random_D(r, n, hi=40, zero_frac=0.25):
+    D = r.integers(0, hi, size=(n, n))
+    D[r.random((n, n)) < zero_frac] = 0
+    return D
+
+
+def check_rounds(plan, D, B, exact):
+    n = len(D)
+    Pm = OS.scaled_matrix(D, B)
+    bm = OS.bmax(D, B)
+    tol = 0 if exact else 1e-9 * float(bm) + 1e-12
+    assert abs(plan["bmax"] - float(bm)) <= tol
+    assert abs(plan["duration"].sum() - float(bm)) <= max(tol, 0) if plan["n_rounds"] else bm == 0
+    assert plan["n_rounds"] <= n * n + 8
+    carried = np.zeros((n, n))
+    left = np.array([[float(v) for v in row] for row in Pm])
+    for dst, tau in zip(plan["dst"], plan["duration"]):
+        live = [j for j in dst if j >= 0]
+        assert len(live) == len(set(live))                      # a receiver hears one sender per round
+        for i, j in enumerate(dst):
+            if j >= 0:
+                assert i != j
+                use = min(left[i, j], tau)
+                left[i, j] -= use
+                carried[i, j] += use
+    assert np.all(np.abs(left) <= (0 if exact else 1e-9 * float(bm) + 1e-12))   # everything delivered
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 8, 16])
+def test_aurora_order_homogeneous_matches_oracle_exactly(n):
+    r = np.random.default_rng(100 + n)
+    for _ in range(5):
+        D = random_D(r, n)
+        plan = P.aurora_order(D)
+        check_rounds(plan, D, None, exact=True)
+        assert plan["bmax"] == float(OS.bmax(D)) == plan["port_bound"]
+        ref = OS.alg1_order(D)
+        assert plan["dest_order"].tolist() == ref["dest_order"]                 # same stated reading
+        assert plan["makespan_order"] == float(ref["makespan"])
+        for i in range(n):
+            for j in range(n):
+                s = ref["start"][i][j]
+                assert plan["start"][i, j] == (-1.0 if s is None else float(s))
+        # the fluid simulation divides rates by fan-in, so doubles round where the oracle's rationals do not
+        assert P.aurora_simulate(D, None, plan["dest_order"]) == pytest.approx(
+            float(OS.simulate(D, None, ref["dest_order"])), rel=1e-12)
+
+
+@pytest.mark.parametrize("n", [2, 3, 4, 8, 16])
+def test_aurora_order_heterogeneous(n):
+    r = np.random.default_rng(200 + n)
+    for _ in range(5):
+        D = random_D(r, n)
+        B = r.uniform(0.5, 1.0, size=n)
+        plan = P.aurora_order(D, B)
+        check_rounds(plan, D, B, exact=False)
+        assert plan["bmax"] == pytest.approx(float(OS.bmax(D, B)), rel=1e-12)
+        assert plan["port_bound"] == pytest.approx(float(OS.port_bound(D, B)), rel=1e-12)
+        assert plan["port_bound"] <= plan["bmax"] * (1 + 1e-12)
+        # the per-destination plan is valid: complete, contention-free, not below the bound
+        Pm = np.array([[float(v) for v in row] for row in OS.scaled_matrix(D, B)])
+        st = plan["start"]
+        assert np.array_equal(st >= 0, Pm > 0)
+        for i in range(n):
+            assert sorted(plan["dest_order"][i].tolist()) == list(range(n))
+            for tl in ([(st[i, j], st[i, j] + Pm[i, j]) for j in range(n) if st[i, j] >= 0],
+                       [(st[j, i], st[j, i] + Pm[j, i]) for j in range(n) if st[j, i] >= 0]):
+                tl.sort()
+                assert all(a1 >= b0 - 1e-9 for (_, b0), (a1, _) in zip(tl[:-1], tl[1:]))
+        assert plan["makespan_order"] >= plan["bmax"] * (1 - 1e-12)
+        got = P.aurora_simulate(D, B, plan["dest_order"])
+        assert got == pytest.approx(float(OS.simulate(D, B, plan["dest_order"].tolist())), rel=1e-9)
+        # with unequal rates a fast receiver can serve two slow senders at once, so the fluid model can
+        # beat the one-sender-per-receiver bound of Appendix B; the per-port bound still holds
+        assert got >= plan["port_bound"] * (1 - 1e-9)
+
+
+def test_simulate_all_orders_against_oracle_n4_and_figure():
+    r = np.random.default_rng(7)
+    D = random_D(r, 4, hi=9)
+    per_src = [list(itertools.permutations([j for j in range(4) if j != i])) for i in range(4)]
+    best = None
+    for combo in itertools.product(*per_src):
+        order = [list(c) + [i] for i, c in enumerate(combo)]
+        got = P.aurora_simulate(D, None, order)
+        assert got == pytest.approx(float(OS.simulate(D, None, combo)), rel=1e-12)
+        best = got if best is None else min(best, got)
+    assert best >= P.aurora_order(D)["bmax"]
+    fig = [[0, 1, 1], [1, 0, 1], [0, 0, 0]]
+    assert P.aurora_simulate(fig, None, [[1, 2, 0], [0, 2, 1], [0, 1, 2]]) == 3.0
+    assert P.aurora_simulate(fig, None, [[1, 2, 0], [2, 0, 1], [0, 1, 2]]) == 2.0
+    plan = P.aurora_order(fig)
+    assert plan["bmax"] == 2.0 and plan["makespan_rounds"] == 2.0 and plan["makespan_order"] == 2.0
+
+
+def test_schedules_for_the_workload_matrices():
+    for name in ("c1_tiny_fp32", "c2_mixtral", "c5_finegrained"):
+        cfg = W.get_config(name)
+        D = W.make_traffic_matrix(cfg)["D"]
+        B = W.make_link_rates(cfg) if cfg.hetero_links else None
+        plan = P.aurora_order(D, B)
+        check_rounds(plan, D, B, exact=B is None)
+        assert plan["makespan_order"] >= plan["bmax"] * (1 - 1e-12)
+
+
+@pytest.mark.parametrize("na,nb", [(1, 1), (2, 2), (3, 3), (4, 4), (6, 6), (2, 4), (3, 4), (4, 8), (8, 8)])
+def test_colocate_match_against_brute_force(na, nb):
+    r = np.random.default_rng(300 + 10 * na + nb)
+    for _ in range(4 if nb >= 8 else 8):
+        Da, Db = r.integers(0, 50, size=(na, na)), r.integers(0, 50, size=(nb, nb))
+        pair, bott = P.colocate_match(Da, Db)
+        want, _ = OM.best_pairing_brute(Da, Db)
+        assert bott == want
+        Wm = OM.pair_weights(Da, Db)
+        assert len(set(pair)) == na and all(0 <= j < nb for j in pair)
+        assert max(Wm[i][pair[i]] for i in range(na)) == want
+
+
+def test_colocate_case1_and_config4_shapes():
+    r = np.random.default_rng(9)
+    for n in (4, 8, 16):
+        A = r.integers(0, 30, size=(n, n)); A = A + A.T
+        Bm = r.integers(0, 30, size=(n, n)); Bm = Bm + Bm.T
+        sa, _ = OM.send_recv(A)
+        sb, _ = OM.send_recv(Bm)
+        assert P.colocate_match(A, Bm)[1] == OM.case1_value(sa, sb)        # Theorem 6
+    # the two colocated models of the workload: 8 experts vs 16 experts on 8 GPUs (one expert each per GPU)
+    Da = W.make_traffic_matrix(W.get_config("c4a_coloc"))["D"]
+    pe = W.make_traffic_matrix(W.get_config("c4b_coloc"))["per_expert"]     # [8 GPUs, 16 experts]
+    Db16 = np.zeros((16, 16), dtype=np.int64)
+    Db16[:8, :] = pe                                                        # expert-level receive pattern
+    pair, bott = P.colocate_match(Da, Db16)
+    assert bott == OM.best_pairing_threshold(Da, Db16)[0]
+    assert len(set(pair)) == 8
