@@ -127,11 +127,13 @@ __global__ __launch_bounds__(256) void rank_kernel(const int32_t* __restrict__ i
         const int s = base + r * 64 + lane;
         if (s < n_slots) {
             const int e = my_e[r];
-            const int rank = cnt[(wave * 4 + r) * E + e] + lane_rank[r];
             int row = -1;
-            if (capacity <= 0 || rank < capacity) {
-                row = seg_start[e] + rank;
-                row_to_slot[row] = s;
+            if (e >= 0 && e < E) {                      // an index outside [0, E) is treated as a dropped slot
+                const int rank = cnt[(wave * 4 + r) * E + e] + lane_rank[r];
+                if (capacity <= 0 || rank < capacity) {
+                    row = seg_start[e] + rank;
+                    row_to_slot[row] = s;
+                }
             }
             slot_to_row[s] = row;
         }

@@ -1,0 +1,208 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle on the same seeded inputs.
+
+Integer results (indices, counts, permutation, copied rows) must be bit-exact.  Floating
+point: fp32 within 1e-5, bf16 within 2e-2, both as max|diff| / max|ref| per tensor.
+"""
+import dataclasses
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from oracle import moe_layer as O
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"fp32": 1e-5, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def H():
+    from tests import harness
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return harness
+
+
+def small(name, **kw):
+    return W.scaled(W.get_config(name), **kw)
+
+
+# reduced shapes the oracle finishes in seconds; several tiles and ragged tails everywhere
+ROUTE_CASES = [
+    W.get_config("c1_tiny_fp32"),
+    small("c1_tiny_fp32", T=3, H=4, E=2, k=1, G=2),
+    small("c1_tiny_fp32", T=37, H=100, E=5, k=3, G=5),
+    small("c2_mixtral", T=203, H=1032),
+    small("c2_mixtral", T=64, H=4096),
+    small("c3_switch", T=517, H=256),
+    small("c4b_coloc", T=130, H=512),
+    small("c5_finegrained", T=301, H=512),
+    small("c5_finegrained", T=65, H=264, E=160, k=9, G=16),
+    small("c1_tiny_fp32", T=50, H=36, E=200, k=16, G=8),
+    small("c2_mixtral", T=33, H=64, E=24, k=4, G=8),
+]
+
+
+def route_inputs(cfg):
+    inp = W.make_layer_inputs(cfg)
+    if inp["gate_bias"] is None and cfg.index % 2 == 1:
+        inp["gate_bias"] = np.linspace(-0.5, 0.5, cfg.E).astype(np.float32)
+    return inp
+
+
+@pytest.mark.parametrize("cfg", ROUTE_CASES, ids=lambda c: "%s-T%d-H%d-E%d-k%d" % (c.name, c.T, c.H, c.E, c.k))
+def test_route(H, cfg):
+    inp = route_inputs(cfg)
+    idx_ref, w_ref, z = O.route(inp["x"], inp["w_gate"], inp["gate_bias"], cfg.k, cfg.renorm)
+    margin = O.route_margin(z, cfg.k).min()
+    assert margin > 1e-9, "seed gives a near tie; bit-exact indices would not be meaningful"
+    sh = H.Share(cfg)
+    x, wg = H.dev(inp["x"], cfg.dtype), H.dev(inp["w_gate"], cfg.dtype)
+    bias = None if inp["gate_bias"] is None else torch.from_numpy(inp["gate_bias"]).to(H.DEV)
+    sh.route(x, wg, bias)
+    torch.cuda.synchronize()
+    assert np.array_equal(H.host(sh.idx), idx_ref)
+    assert H.rel_err(H.host(sh.w), w_ref) < 1e-5
+    assert np.max(np.abs(H.host(sh.w) / w_ref - 1.0)) < 1e-5
+
+
+def test_route_ties_pick_lower_index(H):
+    cfg = small("c2_mixtral", T=96, H=256, E=8, k=3)
+    inp = W.make_layer_inputs(cfg)
+    wg = inp["w_gate"].copy()
+    wg[5] = wg[1]; wg[6] = wg[1]; wg[7] = wg[2]            # duplicated gate rows: exact ties
+    idx_ref, w_ref, _ = O.route(inp["x"], wg, None, cfg.k, cfg.renorm)
+    sh = H.Share(cfg)
+    sh.route(H.dev(inp["x"], cfg.dtype), H.dev(wg, cfg.dtype), None)
+    torch.cuda.synchronize()
+    assert np.array_equal(H.host(sh.idx), idx_ref)
+    assert H.rel_err(H.host(sh.w), w_ref) < 1e-5
+
+
+DISPATCH_CASES = [
+    (W.get_config("c1_tiny_fp32"), 0),
+    (small("c1_tiny_fp32", T=1, H=4, E=2, k=1, G=2), 0),
+    (small("c2_mixtral", T=1500, H=520), 0),
+    (small("c3_switch", T=3000, H=128), None),             # config's own capacity (scaled with T)
+    (small("c3_switch", T=2100, H=64), 7),
+    (small("c5_finegrained", T=1111, H=136), 0),
+    (small("c5_finegrained", T=700, H=64, E=160, k=9, G=16), 30),
+]
+
+
+@pytest.mark.parametrize("cfg,cap", DISPATCH_CASES, ids=lambda v: getattr(v, "name", str(v)))
+def test_traffic_and_dispatch(H, cfg, cap):
+    if cap is not None:
+        cfg = dataclasses.replace(cfg, capacity_factor=0.0)
+    capacity = cfg.capacity if cap is None else cap
+    inp = W.make_layer_inputs(cfg)
+    idx_ref, _, _ = O.route(inp["x"], inp["w_gate"], inp["gate_bias"], cfg.k, cfg.renorm)
+    e2g = inp["expert_to_gpu"]
+    r = np.random.default_rng(cfg.seed_base)
+    orders = [list(range(cfg.G)), list(r.permutation(cfg.G))]
+    if cfg.name == "c1_tiny_fp32" and cfg.G == 4:
+        orders = list(itertools.permutations(range(4)))     # all 24 transmission orders
+    sh = H.Share(cfg)
+    sh.ctx.close()
+    sh.ctx = H.P.MoeCtx(cfg.T, cfg.H, cfg.E, cfg.k, cfg.G, cfg.dtype, cfg.renorm, capacity)
+    x = H.dev(inp["x"], cfg.dtype)
+    sh.idx.copy_(torch.from_numpy(idx_ref))
+    ec, dc, nd, _ = O.traffic(idx_ref, e2g, cfg.G, capacity)
+    sh.traffic(e2g)
+    torch.cuda.synchronize()
+    assert np.array_equal(H.host(sh.expert_count), ec)
+    assert np.array_equal(H.host(sh.dest_count), dc)
+    assert int(sh.n_dropped.item()) == nd
+    if capacity:
+        assert nd > 0
+    for order in orders:
+        ref = O.dispatch(inp["x"], idx_ref, e2g, order, capacity)
+        sh.slot_to_row.fill_(-7); sh.row_to_slot.fill_(-7); sh.send_buf.zero_()
+        sh.dispatch(x, e2g, order)
+        torch.cuda.synchronize()
+        n = ref["n_rows"]
+        assert np.array_equal(H.host(sh.slot_to_row), ref["slot_to_row"])
+        assert np.array_equal(H.host(sh.row_to_slot)[:n], ref["row_to_slot"])
+        assert np.all(H.host(sh.row_to_slot)[n:] == -7)                    # nothing written past the kept rows
+        assert np.array_equal(H.host(sh.seg_offset), ref["seg_offset"])
+        assert np.array_equal(H.host(sh.seg_expert), ref["seg_expert"])
+        assert np.array_equal(H.host(sh.send_buf)[:n], ref["send_buf"])    # bitwise row copies
+        assert not H.host(sh.send_buf)[n:].any()
+    # determinism: a second run gives the same bytes
+    a = sh.slot_to_row.clone()
+    sh.dispatch(x, e2g, orders[-1])
+    torch.cuda.synchronize()
+    assert torch.equal(a, sh.slot_to_row)
+
+
+def make_segments(r, R, nseg, n_local):
+    cuts = np.sort(r.integers(0, R + 1, size=nseg - 1))
+    off = [0] + [int(c) for c in cuts] + [R]
+    exp = [int(v) for v in r.integers(0, n_local, size=nseg)]
+    return off, exp
+
+
+FFN_CASES = [
+    # dtype, act, R, H, F, n_local, nseg
+    ("fp32", 0, 300, 64, 128, 2, 5),
+    ("fp32", 1, 77, 36, 52, 3, 4),
+    ("fp32", 2, 130, 64, 128, 2, 6),
+    ("bf16", 2, 700, 256, 384, 2, 5),
+    ("bf16", 2, 1, 128, 128, 1, 1),
+    ("bf16", 1, 523, 256, 512, 3, 7),
+    ("bf16", 0, 300, 128, 256, 2, 3),
+    ("bf16", 2, 1029, 512, 1408, 4, 9),
+]
+
+
+@pytest.mark.parametrize("dtype,act,R,Hd,F,n_local,nseg", FFN_CASES)
+def test_expert_ffn(H, dtype, act, R, Hd, F, n_local, nseg):
+    cfg = small("c2_mixtral" if dtype == "bf16" else "c1_tiny_fp32", H=Hd, F=F, act=act, dtype=dtype)
+    r = np.random.default_rng(R * 7 + F)
+    recv = W.round_to_dtype(r.standard_normal((R, Hd)).astype(np.float32), dtype)
+    experts = [W.make_expert_weights(cfg, e) for e in range(n_local)]
+    off, exp = make_segments(r, R, nseg, n_local)
+    ref = O.expert_ffn(recv, off, exp, experts, act)
+    out = H.run_ffn(H.dev(recv, dtype), off, exp, [H.weights_to_dev(w, dtype) for w in experts], Hd, F, act, dtype)
+    got = H.host(out)
+    assert np.isfinite(got).all()
+    assert H.rel_err(got, ref) < TOL[dtype]
+
+
+def test_expert_ffn_leaves_rows_outside_segments_untouched(H):
+    cfg = small("c2_mixtral", H=128, F=256)
+    r = np.random.default_rng(5)
+    recv = W.to_bf16_grid(r.standard_normal((400, 128)).astype(np.float32))
+    experts = [W.make_expert_weights(cfg, 0)]
+    out = H.run_ffn(H.dev(recv, "bf16"), [10, 10, 300], [0, 0], [H.weights_to_dev(experts[0], "bf16")], 128, 256, 2, "bf16")
+    got = H.host(out)
+    assert np.isnan(got[:10]).all() and np.isnan(got[300:]).all() and np.isfinite(got[10:300]).all()
+    ref = O.expert_ffn(recv[10:300], [0, 290], [0], experts, 2)
+    assert H.rel_err(got[10:300], ref) < TOL["bf16"]
+
+
+COMBINE_CASES = [W.get_config("c1_tiny_fp32"), small("c2_mixtral", T=333, H=520), small("c3_switch", T=1000, H=64),
+                 small("c5_finegrained", T=257, H=264)]
+
+
+@pytest.mark.parametrize("cfg", COMBINE_CASES, ids=lambda c: c.name)
+@pytest.mark.parametrize("with_shared", [False, True])
+def test_combine(H, cfg, with_shared):
+    inp = W.make_layer_inputs(cfg)
+    idx_ref, w_ref, _ = O.route(inp["x"], inp["w_gate"], inp["gate_bias"], cfg.k, cfg.renorm)
+    cap = cfg.capacity
+    d = O.dispatch(inp["x"], idx_ref, inp["expert_to_gpu"], list(range(cfg.G)), cap)
+    r = np.random.default_rng(11)
+    S = cfg.T * cfg.k
+    ret = W.round_to_dtype(r.standard_normal((S, cfg.H)).astype(np.float32), cfg.dtype)
+    shared = W.round_to_dtype(r.standard_normal((cfg.T, cfg.H)).astype(np.float32), cfg.dtype) if with_shared else None
+    w32 = w_ref.astype(np.float32)
+    ref = O.combine(ret[:d["n_rows"]], d["slot_to_row"], w32, shared)
+    sh = H.Share(cfg)
+    sh.slot_to_row.copy_(torch.from_numpy(d["slot_to_row"]))
+    sh.w.copy_(torch.from_numpy(w32))
+    sh.combine(H.dev(ret, cfg.dtype), None if shared is None else H.dev(shared, cfg.dtype))
+    torch.cuda.synchronize()
+    assert H.rel_err(H.host(sh.y), ref) < (1e-6 if cfg.dtype == "fp32" else 2 ** -8)
