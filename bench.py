@@ -1,0 +1,251 @@
+#!/usr/bin/env python3
+"""Benchmark of one GPU's share of an expert-parallel MoE layer on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input:
+route -> traffic -> dispatch -> expert FFN over the rows this GPU receives -> combine.
+The workload is the Mixtral-shape share: 4096 local tokens, hidden 4096, SwiGLU
+4096 -> 14336 -> 4096, 8 experts top-2 over 8 simulated GPUs; the GPU under test hosts
+the most popular expert and receives the largest column of a Zipf(1.0) traffic matrix.
+All inputs are resident in HBM before the timed region.  One JSON line is printed.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def build_workload(cfg, torch, P, W):
+    """Everything a step needs, resident on the GPU.  Returns a dict of tensors and the step closure."""
+    dev = "cuda:0"
+    tdt = P.TORCH_DTYPE[cfg.dtype]
+
+    def to_dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev).to(tdt).contiguous()
+
+    traffic = W.make_traffic_matrix(cfg)
+    D = traffic["D"].copy()
+    g = int(np.argmax(D.sum(axis=0)))                       # the GPU that receives most sets the layer time
+    inp = W.make_layer_inputs(cfg, g)
+    e2g = inp["expert_to_gpu"]
+    local = [e for e in range(cfg.E) if e2g[e] == g]
+    x, wg = to_dev(inp["x"]), to_dev(inp["w_gate"])
+    bias = None if inp["gate_bias"] is None else torch.from_numpy(inp["gate_bias"]).to(dev)
+    experts = []
+    for e in local:
+        w = W.make_expert_weights(cfg, e)
+        experts.append({k: (to_dev(v) if v is not None else None) for k, v in w.items()})
+    table = P.expert_table(experts)
+
+    T, k, H, F, E, G = cfg.T, cfg.k, cfg.H, cfg.F, cfg.E, cfg.G
+    S = T * k
+    ctx = P.MoeCtx(T, H, E, k, G, cfg.dtype, cfg.renorm, cfg.capacity)
+    i32 = dict(dtype=torch.int32, device=dev)
+    idx = torch.zeros((T, k), **i32)
+    w = torch.zeros((T, k), dtype=torch.float32, device=dev)
+    expert_count, dest_count, n_dropped = torch.zeros(E, **i32), torch.zeros(G, **i32), torch.zeros(1, **i32)
+    send_buf = torch.zeros((S, H), dtype=tdt, device=dev)
+    s2r, r2s = torch.zeros(S, **i32), torch.zeros(S, **i32)
+    seg_offset, seg_expert = torch.zeros(E + 1, **i32), torch.zeros(E, **i32)
+    y = torch.zeros((T, H), dtype=tdt, device=dev)
+
+    # set-up pass: this GPU's own row of the traffic matrix is the measured one
+    P.moe_route(ctx, x, wg, bias, idx, w)
+    P.moe_traffic(ctx, idx, e2g, expert_count, dest_count, n_dropped)
+    torch.cuda.synchronize()
+    own_expert = expert_count.cpu().numpy().astype(np.int64)
+    D[g] = dest_count.cpu().numpy()
+    traffic["per_expert"][g] = own_expert
+    rates = W.make_link_rates(cfg) if cfg.hetero_links else None
+    plan = P.aurora_order(D, rates)                          # offline plan from the statistics
+    dest_order = plan["dest_order"][g]
+    P.moe_dispatch(ctx, x, idx, e2g, dest_order, send_buf, s2r, r2s, seg_offset, seg_expert)
+    torch.cuda.synchronize()
+    so = seg_offset.cpu().numpy()
+    se = seg_expert.cpu().numpy()
+
+    # received rows: sources in the order their flow to g starts in the plan, expert-sorted inside a source
+    start_to_g = plan["start"][:, g]
+    sources = sorted(range(G), key=lambda i: (start_to_g[i] if (i != g and start_to_g[i] >= 0) else np.inf, i))
+    off, exp, self_spans = [0], [], []
+    for i in sources:
+        for li, e in enumerate(local):
+            n = int(traffic["per_expert"][i][e])
+            if n == 0:
+                continue
+            if i == g:
+                p = int(np.nonzero(se == e)[0][0])
+                self_spans.append((off[-1], int(so[p]), int(so[p + 1])))
+            off.append(off[-1] + n)
+            exp.append(li)
+    R = off[-1]
+    recv = torch.empty((R, H), dtype=tdt, device=dev)
+    chunk = 4096
+    for r0 in range(0, R, chunk):                            # rows from other GPUs: seeded N(0,1)
+        n = min(chunk, R - r0)
+        recv[r0:r0 + n] = to_dev(W.generate.make_rows(cfg, W.generate.S_RECV, n, sub=r0 // chunk))
+    ffn_off = torch.tensor(off, **i32)
+    ffn_exp = torch.tensor(exp, **i32)
+    ffn_out = torch.empty((R, H), dtype=tdt, device=dev)
+    ws = torch.empty(P.moe_ffn_workspace_bytes(R, H, F, cfg.act, cfg.dtype), dtype=torch.uint8, device=dev)
+    ret = torch.empty((S, H), dtype=tdt, device=dev)
+    for r0 in range(0, S, chunk):                            # rows returned by other GPUs: seeded N(0,1)
+        n = min(chunk, S - r0)
+        ret[r0:r0 + n] = to_dev(W.generate.make_rows(cfg, W.generate.S_RET, n, sub=r0 // chunk))
+    torch.cuda.synchronize()
+
+    def step():
+        P.moe_route(ctx, x, wg, bias, idx, w)
+        P.moe_traffic(ctx, idx, e2g, expert_count, dest_count, n_dropped)
+        P.moe_dispatch(ctx, x, idx, e2g, dest_order, send_buf, s2r, r2s, seg_offset, seg_expert)
+        for (r0, lo, hi) in self_spans:                      # loop-back part of the first all-to-all
+            recv[r0:r0 + hi - lo].copy_(send_buf[lo:hi], non_blocking=True)
+        P.moe_expert_ffn(recv, R, ffn_off, ffn_exp, len(exp), table, H, F, cfg.act, cfg.dtype, ffn_out, ws)
+        for (r0, lo, hi) in self_spans:                      # loop-back part of the second all-to-all
+            ret[lo:hi].copy_(ffn_out[r0:r0 + hi - lo], non_blocking=True)
+        P.moe_combine(ctx, ret, s2r, w, None, y)
+
+    stages = {
+        "route": lambda: P.moe_route(ctx, x, wg, bias, idx, w),
+        "traffic": lambda: P.moe_traffic(ctx, idx, e2g, expert_count, dest_count, n_dropped),
+        "dispatch": lambda: P.moe_dispatch(ctx, x, idx, e2g, dest_order, send_buf, s2r, r2s, seg_offset, seg_expert),
+        "expert_ffn": lambda: P.moe_expert_ffn(recv, R, ffn_off, ffn_exp, len(exp), table, H, F, cfg.act, cfg.dtype,
+                                               ffn_out, ws),
+        "combine": lambda: P.moe_combine(ctx, ret, s2r, w, None, y),
+    }
+    ffn_timed = lambda: P.moe_expert_ffn_timed(recv, R, ffn_off, ffn_exp, len(exp), table, H, F, cfg.act, cfg.dtype,
+                                               ffn_out, ws)
+    n_kept = int(so[-1])
+    return dict(step=step, stages=stages, ffn_timed=ffn_timed, R=R, g=g, n_kept=n_kept, inp=inp,
+                keep=(ctx, x, wg, bias, experts, table, recv, ret, ffn_out, ws, send_buf))
+
+
+def time_events(torch, fn, reps):
+    """Average milliseconds of fn() over `reps` back-to-back launches, by events on the launch stream."""
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        fn()
+    b.record()
+    b.synchronize()
+    return a.elapsed_time(b) / reps
+
+
+def cpu_baseline(cfg, wl, W):
+    """The oracle, as it stands, on the whole share (about 15 s of fp64 numpy), on this machine's host cores."""
+    from oracle import moe_layer as O
+    frac = 1
+    Ts = max(1, cfg.T // frac)
+    Rs = max(1, wl["R"] // frac)
+    inp = wl["inp"]
+    x = inp["x"][:Ts]
+    experts = [W.make_expert_weights(cfg, e) for e in range(cfg.E) if inp["expert_to_gpu"][e] == wl["g"]][:1]
+    rows = W.generate.make_rows(cfg, W.generate.S_RECV, Rs)
+    t0 = time.perf_counter()
+    idx, w, _ = O.route(x, inp["w_gate"], inp["gate_bias"], cfg.k, cfg.renorm)
+    O.traffic(idx, inp["expert_to_gpu"], cfg.G, cfg.capacity)
+    d = O.dispatch(x, idx, inp["expert_to_gpu"], list(range(cfg.G)), cfg.capacity)
+    out = O.expert_ffn(rows, [0, Rs], [0], experts, cfg.act)
+    ret = np.resize(out, (d["n_rows"], cfg.H))
+    O.combine(ret, d["slot_to_row"], w)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    return {"value": Ts / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+            "sample": "1/%d of the share: %d local tokens routed/dispatched/combined and %d received rows through "
+                      "the expert FFN (inputs generated outside the timed region), fp64 numpy, one run of %.1f s"
+                      % (frac, Ts, Rs, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2_mixtral")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU's share of the layer; there is no multi-GPU path in this build "
+              "(run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2410_17043_amd as P
+    import workloads as W
+    import workloads.generate  # noqa: F401
+
+    if not torch.cuda.is_available():
+        print("bench.py needs the MI355X (no CPU fallback exists)", file=sys.stderr)
+        sys.exit(2)
+    cfg = W.get_config(args.workload)
+    wl = build_workload(cfg, torch, P, W)
+    step = wl["step"]
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(args.steps):
+        step()
+    b.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_per_step = a.elapsed_time(b) / args.steps
+
+    stage_ms = {name: time_events(torch, fn, max(3, args.steps // 2)) for name, fn in wl["stages"].items()}
+    reps = max(3, args.steps // 2)
+    gemm_ms = np.mean([wl["ffn_timed"]() for _ in range(reps)], axis=0)   # tile map, GEMM1 (+act), GEMM2
+
+    R, T, k, H, F, b_el = wl["R"], cfg.T, cfg.k, cfg.H, cfg.F, (2 if cfg.dtype == "bf16" else 4)
+    n_up = 2 if cfg.act == 2 else 1
+    flops_gemm1 = 2.0 * n_up * R * H * F
+    flops_gemm2 = 2.0 * R * H * F
+    achieved = flops_gemm1 / (gemm_ms[1] * 1e-3) / 1e12
+    bytes_dispatch = T * H * b_el + wl["n_kept"] * H * b_el + T * k * 12
+    bytes_combine = wl["n_kept"] * H * b_el + T * H * b_el + T * k * 8
+    bytes_route = T * H * b_el + cfg.E * H * b_el + T * k * 8
+    line = {
+        "metric": "MoE-layer tokens/sec on 1 MI355X", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "T": T, "H": H, "F": F, "E": cfg.E, "k": k, "G": cfg.G,
+                   "received_rows": R, "gpu_under_test": wl["g"], "act": cfg.act},
+        "wall_ms_per_step": wall_ms,
+        "stage_ms": {n: round(v, 4) for n, v in stage_ms.items()},
+        "stage_rate": {
+            "route_GBps": bytes_route / (stage_ms["route"] * 1e-3) / 1e9,
+            "dispatch_GBps": bytes_dispatch / (stage_ms["dispatch"] * 1e-3) / 1e9,
+            "combine_GBps": bytes_combine / (stage_ms["combine"] * 1e-3) / 1e9,
+            "ffn_TFLOPs": (flops_gemm1 + flops_gemm2) / (stage_ms["expert_ffn"] * 1e-3) / 1e12,
+            "ffn_mfma_util": (flops_gemm1 + flops_gemm2) / (stage_ms["expert_ffn"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "gemm2_TFLOPs": flops_gemm2 / (gemm_ms[2] * 1e-3) / 1e12,
+            "tilemap_ms": float(gemm_ms[0]),
+        },
+        "roofline": {"kernel": "gemm_bf16_kernel<SwiGLU> (first FFN GEMM with the activation)", "bound": "mfma",
+                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "launch_ms": float(gemm_ms[1]), "flops_per_launch": flops_gemm1},
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(cfg, wl, W)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

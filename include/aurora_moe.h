@@ -146,6 +146,16 @@ int moe_expert_ffn(const void* recv, int32_t R, const int32_t* seg_offset, const
                    int32_t act, int32_t dtype, void* out, void* workspace, size_t workspace_bytes,
                    void* stream);
 
+/* Diagnostic twin of moe_expert_ffn (same arguments, same result): records HIP
+ * events on `stream` around each of its kernels, WAITS for the last one, and
+ * returns the durations in milliseconds in ms_out (HOST [3]): tile map, first GEMM
+ * with the activation (Sec. 2.1's FFN up-projection), second GEMM.  For measurement
+ * only: unlike every other device entry point it synchronises with the host. */
+int moe_expert_ffn_timed(const void* recv, int32_t R, const int32_t* seg_offset, const int32_t* seg_expert,
+                         int32_t nseg, const moe_expert_w* experts, int32_t n_local, int32_t H, int32_t F,
+                         int32_t act, int32_t dtype, void* out, void* workspace, size_t workspace_bytes,
+                         void* stream, float* ms_out);
+
 /* Aggregation (Sec. 2.1): y[t] = sum_j topk_w[t,j] * ret[slot_to_row[t*k+j]] over
  * kept slots (+ shared_out[t]).  `ret` is in send-buffer row order: the second
  * all-to-all reverses the first with equal sizes (Sec. 2.2).

@@ -1,7 +1,7 @@
 """MI355X-native MoE-layer share (Aurora's data-parallel hot path): HIP kernels behind a C ABI.
 
 Importing this package loads libaurora_moe.so; it raises if the library has not been
-built (`python -m paper_2410_17043_amd.build`).  There is no CPU or PyTorch fallback.
+built (`python paper_2410_17043_amd/build.py`).  There is no CPU or PyTorch fallback.
 """
 from . import _lib
 
@@ -9,9 +9,9 @@ _lib.load()
 
 from .api import (  # noqa: E402
     F32, BF16, ACT_SILU_MLP, ACT_GELU_MLP, ACT_SWIGLU, TORCH_DTYPE, MoeError, MoeCtx, moe_route, moe_traffic,
-    moe_dispatch, moe_ffn_workspace_bytes, expert_table, moe_expert_ffn, moe_combine, aurora_order,
+    moe_dispatch, moe_ffn_workspace_bytes, expert_table, moe_expert_ffn, moe_expert_ffn_timed, moe_combine, aurora_order,
     aurora_simulate, colocate_match)
 
 __all__ = ["F32", "BF16", "ACT_SILU_MLP", "ACT_GELU_MLP", "ACT_SWIGLU", "TORCH_DTYPE", "MoeError", "MoeCtx",
            "moe_route", "moe_traffic", "moe_dispatch", "moe_ffn_workspace_bytes", "expert_table",
-           "moe_expert_ffn", "moe_combine", "aurora_order", "aurora_simulate", "colocate_match"]
+           "moe_expert_ffn", "moe_expert_ffn_timed", "moe_combine", "aurora_order", "aurora_simulate", "colocate_match"]

@@ -35,6 +35,8 @@ SIGNATURES = {
     "moe_ffn_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32, _i32]),
     "moe_expert_ffn": (C.c_int, [_vp, _i32, _vp, _vp, _i32, C.POINTER(moe_expert_w), _i32, _i32, _i32, _i32, _i32,
                                  _vp, _vp, _sz, _vp]),
+    "moe_expert_ffn_timed": (C.c_int, [_vp, _i32, _vp, _vp, _i32, C.POINTER(moe_expert_w), _i32, _i32, _i32, _i32, _i32,
+                                       _vp, _vp, _sz, _vp, C.POINTER(C.c_float)]),
     "moe_combine": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "aurora_order": (C.c_int, [_i32, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(aurora_schedule)]),
     "aurora_schedule_free": (None, [C.POINTER(aurora_schedule)]),
@@ -53,7 +55,7 @@ def load():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise ImportError(
-                "libaurora_moe.so is not built: run `python -m paper_2410_17043_amd.build` "
+                "libaurora_moe.so is not built: run `python paper_2410_17043_amd/build.py` "
                 "(this package has no CPU or PyTorch fallback)")
         lib = C.CDLL(LIB_PATH)
         for name, (res, args) in SIGNATURES.items():

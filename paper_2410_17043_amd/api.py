@@ -113,6 +113,16 @@ def moe_expert_ffn(recv, R, seg_offset, seg_expert, nseg, experts, H, F, act, dt
         _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()))
 
 
+def moe_expert_ffn_timed(recv, R, seg_offset, seg_expert, nseg, experts, H, F, act, dtype, out, workspace):
+    """Measurement twin of moe_expert_ffn; returns (ms_tilemap, ms_gemm1, ms_gemm2) and synchronises."""
+    tab = experts if isinstance(experts, C.Array) else expert_table(experts)
+    ms = (C.c_float * 3)()
+    _check("moe_expert_ffn_timed", _lib.load().moe_expert_ffn_timed(
+        _ptr(recv), R, _ptr(seg_offset), _ptr(seg_expert), nseg, tab, len(tab), H, F, act, _DT[dtype], _ptr(out),
+        _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(), ms))
+    return tuple(ms)
+
+
 def moe_combine(ctx, ret, slot_to_row, topk_w, shared_out, y):
     _check("moe_combine", ctx.lib.moe_combine(ctx.handle, _ptr(ret), _ptr(slot_to_row), _ptr(topk_w),
                                               _ptr(shared_out), _ptr(y), _stream()))

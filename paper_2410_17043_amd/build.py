@@ -1,6 +1,6 @@
 """Builds libaurora_moe.so in-tree with hipcc for gfx950 (cross-compiles without a GPU).
 
-    python -m paper_2410_17043_amd.build
+    python paper_2410_17043_amd/build.py
 """
 from __future__ import annotations
 

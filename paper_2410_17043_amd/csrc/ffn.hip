@@ -372,10 +372,9 @@ extern "C" size_t moe_ffn_workspace_bytes(int32_t R_max, int32_t H, int32_t F, i
     return tilemap_bytes(R_max) + align256((size_t)R_max * F * elem_size(dtype)) + 256;
 }
 
-extern "C" int moe_expert_ffn(const void* recv, int32_t R, const int32_t* seg_offset, const int32_t* seg_expert,
-                              int32_t nseg, const moe_expert_w* experts, int32_t n_local, int32_t H, int32_t F,
-                              int32_t act, int32_t dtype, void* out, void* workspace, size_t workspace_bytes,
-                              void* stream) {
+static int ffn_impl(const void* recv, int32_t R, const int32_t* seg_offset, const int32_t* seg_expert, int32_t nseg,
+                    const moe_expert_w* experts, int32_t n_local, int32_t H, int32_t F, int32_t act, int32_t dtype,
+                    void* out, void* workspace, size_t workspace_bytes, hipStream_t st, hipEvent_t* ev) {
     if (!recv || !seg_offset || !seg_expert || !experts || !out || !workspace)
         return moe_set_error(MOE_EINVAL, "moe_expert_ffn: NULL argument");
     if (R < 0 || nseg < 0 || H <= 0 || F <= 0) return moe_set_error(MOE_EINVAL, "moe_expert_ffn: negative size");
@@ -402,24 +401,63 @@ extern "C" int moe_expert_ffn(const void* recv, int32_t R, const int32_t* seg_of
         tab.w_up[e] = experts[e].w_up;
         tab.w_down[e] = experts[e].w_down;
     }
-    if (R == 0 || nseg == 0) return MOE_OK;
-    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (R == 0 || nseg == 0) {
+        if (ev) for (int i = 0; i < 4; ++i) MOE_HIP(hipEventRecord(ev[i], st));
+        return MOE_OK;
+    }
     TileMap m = tilemap_at(workspace, R);
     void* hmid = reinterpret_cast<char*>(workspace) + tilemap_bytes(R);
     const int bm = (dtype == MOE_BF16) ? BM : 64;
+    if (ev) MOE_HIP(hipEventRecord(ev[0], st));
     hipLaunchKernelGGL(tilemap_kernel, dim3(1), dim3(256), 0, st, seg_offset, seg_expert, nseg, R, bm, n_local, m);
     MOE_LAUNCH_CHECK("tilemap_kernel");
+    if (ev) MOE_HIP(hipEventRecord(ev[1], st));
     int rc;
     if (dtype == MOE_BF16) {
         if (act == MOE_ACT_SWIGLU) rc = launch_bf16<EPI_SWIGLU>(recv, H, m, tab, 0, 1, F, H, hmid, F, R, nseg, st);
         else if (act == MOE_ACT_GELU_MLP) rc = launch_bf16<EPI_GELU>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, st);
         else rc = launch_bf16<EPI_SILU>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, st);
         if (rc != MOE_OK) return rc;
-        return launch_bf16<EPI_PLAIN>(hmid, F, m, tab, 2, 2, H, F, out, H, R, nseg, st);
+        if (ev) MOE_HIP(hipEventRecord(ev[2], st));
+        rc = launch_bf16<EPI_PLAIN>(hmid, F, m, tab, 2, 2, H, F, out, H, R, nseg, st);
+    } else {
+        if (act == MOE_ACT_SWIGLU) rc = launch_f32<EPI_SWIGLU>(recv, H, m, tab, 0, 1, F, H, hmid, F, R, nseg, st);
+        else if (act == MOE_ACT_GELU_MLP) rc = launch_f32<EPI_GELU>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, st);
+        else rc = launch_f32<EPI_SILU>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, st);
+        if (rc != MOE_OK) return rc;
+        if (ev) MOE_HIP(hipEventRecord(ev[2], st));
+        rc = launch_f32<EPI_PLAIN>(hmid, F, m, tab, 2, 2, H, F, out, H, R, nseg, st);
     }
-    if (act == MOE_ACT_SWIGLU) rc = launch_f32<EPI_SWIGLU>(recv, H, m, tab, 0, 1, F, H, hmid, F, R, nseg, st);
-    else if (act == MOE_ACT_GELU_MLP) rc = launch_f32<EPI_GELU>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, st);
-    else rc = launch_f32<EPI_SILU>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, st);
     if (rc != MOE_OK) return rc;
-    return launch_f32<EPI_PLAIN>(hmid, F, m, tab, 2, 2, H, F, out, H, R, nseg, st);
+    if (ev) MOE_HIP(hipEventRecord(ev[3], st));
+    return MOE_OK;
+}
+
+extern "C" int moe_expert_ffn(const void* recv, int32_t R, const int32_t* seg_offset, const int32_t* seg_expert,
+                              int32_t nseg, const moe_expert_w* experts, int32_t n_local, int32_t H, int32_t F,
+                              int32_t act, int32_t dtype, void* out, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+    return ffn_impl(recv, R, seg_offset, seg_expert, nseg, experts, n_local, H, F, act, dtype, out, workspace,
+                    workspace_bytes, reinterpret_cast<hipStream_t>(stream), nullptr);
+}
+
+extern "C" int moe_expert_ffn_timed(const void* recv, int32_t R, const int32_t* seg_offset, const int32_t* seg_expert,
+                                    int32_t nseg, const moe_expert_w* experts, int32_t n_local, int32_t H, int32_t F,
+                                    int32_t act, int32_t dtype, void* out, void* workspace, size_t workspace_bytes,
+                                    void* stream, float* ms_out) {
+    if (!ms_out) return moe_set_error(MOE_EINVAL, "moe_expert_ffn_timed: ms_out is NULL");
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+    int rc = MOE_OK;
+    for (int i = 0; i < 4 && rc == MOE_OK; ++i)
+        if (hipEventCreate(&ev[i]) != hipSuccess) rc = moe_set_error(MOE_EHIP, "hipEventCreate failed");
+    if (rc == MOE_OK)
+        rc = ffn_impl(recv, R, seg_offset, seg_expert, nseg, experts, n_local, H, F, act, dtype, out, workspace,
+                      workspace_bytes, st, ev);
+    if (rc == MOE_OK && hipEventSynchronize(ev[3]) != hipSuccess) rc = moe_set_error(MOE_EHIP, "hipEventSynchronize failed");
+    for (int i = 0; i < 3 && rc == MOE_OK; ++i)
+        if (hipEventElapsedTime(&ms_out[i], ev[i], ev[i + 1]) != hipSuccess) rc = moe_set_error(MOE_EHIP, "hipEventElapsedTime failed");
+    for (int i = 0; i < 4; ++i)
+        if (ev[i]) (void)hipEventDestroy(ev[i]);
+    return rc;
 }

@@ -6,6 +6,7 @@ import numpy as np
 import torch
 
 import paper_2410_17043_amd as P
+import workloads as W
 
 DEV = "cuda:0"
 
@@ -74,3 +75,75 @@ def rel_err(got, ref):
     """Normwise error: max |got - ref| / max |ref|."""
     ref = np.asarray(ref, dtype=np.float64)
     return float(np.max(np.abs(np.asarray(got, dtype=np.float64) - ref)) / max(np.max(np.abs(ref)), 1e-300))
+
+
+def run_emulated_cluster(cfg, dest_orders=None, n_shared=0):
+    """The whole layer over cfg.G simulated GPUs on the one real GPU.
+
+    Every simulated GPU runs route / traffic / dispatch through the library; the two
+    all-to-alls are plain device copies of whole segments (they stand in for the wire);
+    each simulated GPU then runs the grouped FFN over what it received, results travel
+    back to the rows they came from, and combine forms y.  Returns the per-GPU inputs,
+    the measured traffic matrix and y per GPU (host arrays).
+    """
+    G, E, H_, F = cfg.G, cfg.E, cfg.H, cfg.F
+    inputs = [W.make_layer_inputs(cfg, g) for g in range(G)]
+    e2g = inputs[0]["expert_to_gpu"]
+    experts_host = [W.make_expert_weights(cfg, e) for e in range(E)]
+    experts_dev = [weights_to_dev(w, cfg.dtype) for w in experts_host]
+    shared_host = [W.make_expert_weights(cfg, s, shared=True) for s in range(n_shared)]
+    wg = dev(inputs[0]["w_gate"], cfg.dtype)
+    bias = None if inputs[0]["gate_bias"] is None else torch.from_numpy(inputs[0]["gate_bias"]).to(DEV)
+    shares, xs = [], []
+    D = np.zeros((G, G), dtype=np.int64)
+    for g in range(G):
+        sh = Share(cfg)
+        x = dev(inputs[g]["x"], cfg.dtype)
+        sh.route(x, wg, bias)
+        sh.traffic(e2g)
+        torch.cuda.synchronize()
+        D[g] = host(sh.dest_count)
+        shares.append(sh)
+        xs.append(x)
+    if dest_orders is None:
+        dest_orders = P.aurora_order(D)["dest_order"]          # offline plan from the measured statistics
+    for g in range(G):
+        shares[g].dispatch(xs[g], e2g, dest_orders[g])
+    torch.cuda.synchronize()
+    seg = [(host(sh.seg_offset), host(sh.seg_expert)) for sh in shares]
+    rets = [torch.zeros_like(sh.send_buf) for sh in shares]
+    for dst in range(G):
+        local = [e for e in range(E) if e2g[e] == dst]
+        chunks, off, exp, origin = [], [0], [], []
+        for src in range(G):
+            so, se = seg[src]
+            for i, e in enumerate(se):
+                if e2g[e] == dst and so[i + 1] > so[i]:
+                    chunks.append(shares[src].send_buf[so[i]:so[i + 1]])          # first all-to-all
+                    off.append(off[-1] + int(so[i + 1] - so[i]))
+                    exp.append(local.index(int(e)))
+                    origin.append((src, int(so[i]), int(so[i + 1])))
+        if not chunks:
+            continue
+        recv = torch.cat(chunks).contiguous()
+        out = run_ffn(recv, off, exp, [experts_dev[e] for e in local], H_, F, cfg.act, cfg.dtype)
+        for i, (src, lo, hi) in enumerate(origin):
+            rets[src][lo:hi] = out[off[i]:off[i + 1]]                             # second all-to-all (reversed)
+    ys = []
+    shared_dev = None
+    if n_shared:
+        # the shared experts' outputs add up, which equals ONE expert whose inner dimension is the
+        # concatenation of theirs: weights are stacked once at set-up, then a single FFN call
+        cat = {"w1": np.concatenate([w["w1"] for w in shared_host]),
+               "w_up": np.concatenate([w["w_up"] for w in shared_host]) if shared_host[0]["w_up"] is not None else None,
+               "w_down": np.concatenate([w["w_down"] for w in shared_host], axis=1)}
+        shared_dev = weights_to_dev(cat, cfg.dtype)
+    for g in range(G):
+        sh_out = None
+        if n_shared:
+            sh_out = run_ffn(xs[g], [0, cfg.T], [0], [shared_dev], H_, F * n_shared, cfg.act, cfg.dtype)
+        shares[g].combine(rets[g], sh_out)
+        torch.cuda.synchronize()
+        ys.append(host(shares[g].y))
+    return {"inputs": inputs, "experts": experts_host, "shared": shared_host, "D": D, "y": ys,
+            "dest_orders": np.asarray(dest_orders)}
