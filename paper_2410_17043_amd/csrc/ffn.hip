@@ -9,14 +9,16 @@
 // turns the segment list into a list of M-tiles (adjacent segments of the same
 // expert are merged, tiles never straddle experts), so nothing waits for the host.
 //
-// bf16 path: 256x256x64 block tile, 4 waves in 2x2, each wave 128x128 = 4x4 tiles of
-// v_mfma_f32_32x32x16_bf16, fp32 accumulators; operands staged through LDS with an
-// XOR swizzle of the 16-byte k-chunks (conflict-free ds_read_b128); the next k-tile
-// is fetched into registers while the current one is multiplied.  For SwiGLU the B
-// tile holds 128 gate rows and 128 up rows arranged so that a wave owns the gate and
-// the up product of the same 64 columns: the activation is applied on registers and
-// the intermediate is written once, in bf16.  Block ids are remapped so that the
-// blocks that share an XCD's L2 work on neighbouring tiles.
+// bf16 path: 256x256 block tile, 32-wide k-tiles, 4 waves in 2x2, each wave 128x128 = 4x4
+// tiles of v_mfma_f32_32x32x16_bf16 with fp32 accumulators (256 accumulator registers per
+// lane); operands go global -> LDS directly (no register staging) through a 5-stage ring that
+// fills the whole 160 KB LDS, in an XOR-swizzled layout that makes every ds_read_b128 of an
+// MFMA operand conflict-free on the 64 LDS banks.  Loads, LDS reads and MFMAs are software
+// pipelined by hand (see the kernel).  For SwiGLU the B tile holds 128 gate rows and 128 up
+// rows arranged so that a wave owns the gate and the up product of the same 64 columns: the
+// activation is applied on registers and the intermediate is written once, in bf16, as whole
+// 128-byte lines after a transpose through LDS.  Block ids are remapped so that the blocks
+// that share an XCD's L2 work on neighbouring tiles.
 //
 // fp32 path (correctness configuration): plain 64x64x16 LDS-tiled vector-ALU GEMM.
 #include "common.h"
@@ -183,31 +185,62 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__
 
 // ------------------------------------------------------------------------------------ bf16 MFMA
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int BM = 256, BN = 256, BK = 32, STAGES = 4;
+constexpr int BM = 256, BN = 256, BK = 32, STAGES = 5;
 constexpr int kTileBytes = BM * BK * 2;        // one 256 x 32 bf16 operand tile: 16 KB
 constexpr int kStageBytes = 2 * kTileBytes;    // A tile then B tile
-constexpr int kLdsBytes = STAGES * kStageBytes;
+constexpr int kLdsBytes = STAGES * kStageBytes;   // 160 KB: the whole LDS of a CU
 
 // An operand tile is stored as 16 blocks of 16 rows; a block is 1 KB = 64 slots of
 // 16 bytes and is filled by ONE wave-wide direct-to-LDS load (lane l fills slot l).
-// Inside a block, 16-byte chunk c (0..3) of row r (0..15) sits in slot
-//     (r/2)*8 + (((r%2)*4 + c) ^ (r/2))
-// so that the 8 lanes served together by a ds_read_b128 (8 consecutive rows, same
-// chunk) touch 8 different 16-byte bank groups.
-__device__ __forceinline__ int slot_of(int r, int c) { return ((r >> 1) << 3) + ((((r & 1) << 2) + c) ^ (r >> 1)); }
+// Inside a block the rows are kept row-major (4 slots per row, so 4 neighbouring
+// lanes fetch 64 contiguous bytes of one row from memory), with the 16-byte chunk
+// index XOR-ed by row/4:
+//     slot(r, c) = 4*r + (c ^ (r >> 2)),   r = 0..15, c = 0..3.
+// The LDS has 64 banks and serves a ds_read_b128 sixteen lanes at a time; the 16
+// lanes of one MFMA operand read (16 consecutive rows, same chunk) then fall on
+// slots with 16 different values of slot % 16, i.e. on all 64 banks once.
+__device__ __forceinline__ int slot_of(int r, int c) { return (r << 2) + (c ^ (r >> 2)); }
 // inverse for the loading lane: which (row, chunk) of the block lane l must fetch
 __device__ __forceinline__ void rc_of_slot(int l, int* r, int* c) {
-    const int rp = l >> 3, v = (l & 7) ^ rp;
-    *r = rp * 2 + (v >> 2);
-    *c = v & 3;
+    *r = l >> 2;
+    *c = (l & 3) ^ (l >> 4);
 }
 // byte offset of (row, chunk) inside a 256-row tile
 __device__ __forceinline__ int tile_off(int row, int c) { return ((row >> 4) << 10) + (slot_of(row & 15, c) << 4); }
 
-// SwiGLU tile row r (0..255) -> (matrix, column): wave-column wn = r / 128 owns 64 output
-// columns; its first 64 tile rows are W1 rows, the next 64 the Wu rows of the same columns.
+__device__ __forceinline__ float fast_silu(float a) {
+    return a * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.44269504088896f * a));
+}
+template <int EPI> __device__ __forceinline__ float epilogue_bf16(float a, float b) {
+    if (EPI == EPI_SILU) return fast_silu(a);
+    if (EPI == EPI_GELU) return gelu_tanh_f(a);
+    if (EPI == EPI_SWIGLU) return fast_silu(a) * b;
+    return a;
+}
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    const f32x2 v = {lo, hi};
+    const bf16x2 b = __builtin_convertvector(v, bf16x2);      // round to nearest even in hardware
+    return *reinterpret_cast<const uint32_t*>(&b);
+}
+
+// C[r, n] = epi(sum_k A[r,k] B0[n,k] , sum_k A[r,k] B1[n,k]) for one 256-row M-tile and one
+// N-tile.  SwiGLU: the B tile's 256 rows are, per wave-column wn (64 output columns), 64 rows
+// of W1 followed by the 64 rows of Wu for the same columns, so the gate and the up product of
+// a column live in the same lane and the activation needs no exchange.
+//
+// Pipeline: 5 LDS stages of one 32-wide k-tile each (160 KB).  Loads are direct-to-LDS and
+// issued in PAIRS of k-tiles (2q, 2q+1) every second iteration, interleaved so that the two
+// halves of every 128-byte memory line are requested back to back: half-line requests that
+// come a whole k-tile apart cost about twice the L2 bandwidth.  The pair (kt+4, kt+5) is issued
+// in iteration kt (kt even) and first needed 2.5 iterations later.
+// The MFMAs are issued as D = B . A^T (operands swapped), so a lane ends up with 4 consecutive
+// output COLUMNS of one row: the epilogue packs them to 8 bytes, transposes through LDS and
+// writes whole 128-byte lines.
 template <int EPI>
 __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __restrict__ A, int lda, TileMap m,
                                                            ExpertTable tab, int which0, int which1, int N, int K,
@@ -215,6 +248,8 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
                                                            int max_tiles_m) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     constexpr int NOUT = (EPI == EPI_SWIGLU) ? 128 : 256;                  // output columns per block
+    constexpr int NW = NOUT / 2;                                           // output columns per wave
+    constexpr int NJ = NW / 32;                                            // 32-wide output column tiles per wave
     const int n_tiles_m = *m.n_tiles;
     int tile_m, tile_n;
     tile_of_block(blockIdx.x, gridDim.x, max_tiles_m, tiles_n, &tile_m, &tile_n);
@@ -252,18 +287,27 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
         }
         b_src[i] = Bm + (size_t)min(col, N - 1) * K + lc * 8;
     }
-    auto issue = [&](int kt, int buf) {
-        unsigned char* sa = lds + buf * kStageBytes;
-        unsigned char* sb = sa + kTileBytes;
-        const int k0 = kt * BK;
+    const int nk = K / BK;                                   // even: K is a multiple of 64
+    // k-tiles t and t+1 (t even) into the stages t % 5 and (t+1) % 5; past the end the last pair is
+    // fetched again (into stages nobody reads) so that the count of outstanding loads stays uniform
+    auto issue_part = [&](int t, int i_lo, int i_hi) {
+        t = min(t, nk - 2);
+        unsigned char* s0 = lds + (t % STAGES) * kStageBytes;
+        unsigned char* s1 = lds + ((t + 1) % STAGES) * kStageBytes;
+        const int k0 = t * BK;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            __builtin_amdgcn_global_load_lds(a_src[i] + k0, (__attribute__((address_space(3))) void*)(sa + (wave + 4 * i) * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds(b_src[i] + k0, (__attribute__((address_space(3))) void*)(sb + (wave + 4 * i) * 1024), 16, 0, 0);
+            if (i < i_lo || i >= i_hi) continue;
+            const int blk = (wave + 4 * i) * 1024;
+            __builtin_amdgcn_global_load_lds(a_src[i] + k0, (__attribute__((address_space(3))) void*)(s0 + blk), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(a_src[i] + k0 + BK, (__attribute__((address_space(3))) void*)(s1 + blk), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(b_src[i] + k0, (__attribute__((address_space(3))) void*)(s0 + kTileBytes + blk), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(b_src[i] + k0 + BK, (__attribute__((address_space(3))) void*)(s1 + kTileBytes + blk), 16, 0, 0);
         }
     };
+    auto issue_pair = [&](int t) { issue_part(t, 0, 4); };
 
-    f32x16 acc[4][4];
+    f32x16 acc[4][4];                                        // [m-tile i][n-tile j], holds D^T: rows n, columns m
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -271,9 +315,8 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    const int nk = K / BK;
-#pragma unroll
-    for (int p = 0; p < STAGES - 1; ++p) issue(min(p, nk - 1), p);
+    issue_pair(0);
+    issue_pair(2);
 
     const int fr = lane & 31, fk = lane >> 5;      // fragment row within a 32-row tile, which k-half
     int a_off[4][2], b_off[4][2];                  // byte offsets inside a stage, per 32-row tile and k-step
@@ -285,50 +328,113 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
             b_off[i][s] = kTileBytes + tile_off(wn * 128 + i * 32 + fr, 2 * s + fk);
         }
 
-    for (int kt = 0; kt < nk; ++kt) {
-        // tile kt has landed once at most the 2 younger tiles (8 loads each per wave) are outstanding
-        // (a bare barrier: __syncthreads() would add a fence that waits for ALL outstanding loads)
-        __builtin_amdgcn_s_waitcnt(0x4F70);        // vmcnt(16)
-        __builtin_amdgcn_s_barrier();
-        issue(min(kt + STAGES - 1, nk - 1), (kt + STAGES - 1) % STAGES);
-        const unsigned char* st = lds + (kt % STAGES) * kStageBytes;
+    auto load_frags = [&](bf16x8 (&af)[4], bf16x8 (&bfr)[4], const unsigned char* st, int s) {
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            bf16x8 af[4], bfr[4];
+        for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const bf16x8*>(st + a_off[i][s]);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const bf16x8*>(st + a_off[i][s]);
+        for (int j = 0; j < 4; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(st + b_off[j][s]);
+    };
+    auto mma = [&](const bf16x8 (&af)[4], const bf16x8 (&bfr)[4]) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(st + b_off[j][s]);
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-        }
-    }
-    __builtin_amdgcn_s_waitcnt(0x0F70);            // vmcnt(0): no load may still target LDS when the block ends
+            for (int j = 0; j < 4; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+    };
 
-    // epilogue: acc[i][j][e] is row (e/4)*8 + (lane/32)*4 + e%4, column lane%32 of tile (i, j)
+    // Software pipeline, two k-tiles per trip, four phases of 16 MFMAs each:
+    //   A(kt)   read fragments (kt, k-step 1)     | MFMAs (kt, step 0)   | load group 3 of pair (kt+2, kt+3)
+    //   barrier: every wave is done with the stages of tiles kt-1 and kt
+    //   B(kt)   read fragments (kt+1, step 0)     | MFMAs (kt, step 1)   | load group 0 of pair (kt+4, kt+5)
+    //   A(kt+1) read fragments (kt+1, step 1)     | MFMAs (kt+1, step 0) | load group 1
+    //   wait until only groups 0 and 1 (8 loads per wave) are outstanding: pair (kt+2, kt+3) is in LDS; barrier
+    //   B(kt+1) read fragments (kt+2, step 0)     | MFMAs (kt+1, step 1) | load group 2
+    // A group is 4 loads per wave (one 16-row block of A and of B, both k-tiles of the pair).  The
+    // loads are spread evenly, one per four MFMAs: a CU sustains roughly one wave-load per 40 clocks
+    // when the lines come from HBM, and a load that cannot be accepted stalls the wave's MFMA issue too.
+    // A bare s_barrier is used: __syncthreads() would add a fence that waits for ALL outstanding loads.
+    bf16x8 a0[4], b0[4], a1[4], b1[4];
+    __builtin_amdgcn_s_waitcnt(0x4F70);            // vmcnt(16): pair (0, 1) is in LDS
+    __builtin_amdgcn_s_barrier();
+    load_frags(a0, b0, lds, 0);
+#define MOE_PHASE_SCHED()                                                                      \
+    _Pragma("unroll") for (int q = 0; q < 8; ++q) {   /* (MFMA, LDS read) x 8 */                \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                     \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                     \
+    }                                                                                          \
+    _Pragma("unroll") for (int q = 0; q < 4; ++q) {   /* (MFMA, MFMA, global->LDS load) x 4 */  \
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                     \
+        __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                     \
+    }
+    for (int kt = 0; kt < nk; kt += 2) {
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(a1, b1, lds + (kt % STAGES) * kStageBytes, 1);
+        if (kt > 0) issue_part(kt + 2, 3, 4);
+        mma(a0, b0);
+        MOE_PHASE_SCHED()
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(a0, b0, lds + ((kt + 1) % STAGES) * kStageBytes, 0);
+        issue_part(kt + 4, 0, 1);
+        mma(a1, b1);
+        MOE_PHASE_SCHED()
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(a1, b1, lds + ((kt + 1) % STAGES) * kStageBytes, 1);
+        issue_part(kt + 4, 1, 2);
+        mma(a0, b0);
+        MOE_PHASE_SCHED()
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(0x0F78);        // vmcnt(8)
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        load_frags(a0, b0, lds + ((kt + 2) % STAGES) * kStageBytes, 0);
+        issue_part(kt + 4, 2, 3);
+        mma(a1, b1);
+        MOE_PHASE_SCHED()
+        __builtin_amdgcn_sched_barrier(0);
+    }
+#undef MOE_PHASE_SCHED
+    // no load may still target LDS, and no wave may still read operands, when LDS is reused below
+    __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0) lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+
+    // Epilogue.  acc[i][j][e] is output row  i*32 + lane%32  and output column
+    // j*32 + (e/4)*8 + (lane/32)*4 + e%4  of this wave's 128 x (NJ*32) block.
+    constexpr int PITCH = NW * 2 + 8;              // bytes; the +8 spreads the 32 rows of a write over all banks
+    unsigned char* region = lds + wave * (128 * PITCH);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int r = wm * 128 + i * 32 + (e >> 2) * 8 + fk * 4 + (e & 3);
-            if (r >= nrows) continue;
-            uint16_t* crow = C + (size_t)(row0 + r) * ldc;
-            if (EPI == EPI_SWIGLU) {
+        for (int j = 0; j < NJ; ++j)
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const int col = n0 + wn * 64 + j * 32 + fr;
-                    if (col < N) crow[col] = (uint16_t)f32_to_bf16_bits(epilogue<EPI>(acc[i][j][e], acc[i][j + 2][e]));
+            for (int g = 0; g < 4; ++g) {
+                float v[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const float up = (EPI == EPI_SWIGLU) ? acc[i][j + 2][4 * g + t] : 0.f;
+                    v[t] = epilogue_bf16<EPI>(acc[i][j][4 * g + t], up);
                 }
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int col = n0 + wn * 128 + j * 32 + fr;
-                    if (col < N) crow[col] = (uint16_t)f32_to_bf16_bits(epilogue<EPI>(acc[i][j][e], 0.f));
-                }
+                const u32x2 p = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+                *reinterpret_cast<u32x2*>(region + (i * 32 + fr) * PITCH + (j * 32 + g * 8 + fk * 4) * 2) = p;
             }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    constexpr int LPR = NW * 2 / 16;               // lanes per output row (16 bytes each)
+    constexpr int RPI = 64 / LPR;                  // rows per store instruction
+    const int sub_r = lane / LPR, sub_c = lane % LPR;
+    const int col = n0 + wn * NW + sub_c * 8;
+#pragma unroll 4
+    for (int it = 0; it < 128 / RPI; ++it) {
+        const int r = it * RPI + sub_r;            // row inside this wave's 128
+        const unsigned char* src = region + r * PITCH + sub_c * 16;
+        const u32x2 lo = *reinterpret_cast<const u32x2*>(src);
+        const u32x2 hi = *reinterpret_cast<const u32x2*>(src + 8);
+        const int gr = wm * 128 + r;
+        if (gr < nrows && col < N) {
+            const u32x4 q = {lo.x, lo.y, hi.x, hi.y};
+            *reinterpret_cast<u32x4*>(C + (size_t)(row0 + gr) * ldc + col) = q;
         }
     }
 }
