@@ -104,41 +104,61 @@ def build_workload(cfg, torch, P, W):
         ret[r0:r0 + n] = to_dev(W.generate.make_rows(cfg, W.generate.S_RET, n, sub=r0 // chunk))
     torch.cuda.synchronize()
 
+    b_route = P.bind_route(ctx, x, wg, bias, idx, w)
+    b_traffic = P.bind_traffic(ctx, idx, e2g, expert_count, dest_count, n_dropped)
+    b_dispatch = P.bind_dispatch(ctx, x, idx, e2g, dest_order, send_buf, s2r, r2s, seg_offset, seg_expert)
+    b_ffn = P.bind_expert_ffn(recv, R, ffn_off, ffn_exp, len(exp), table, H, F, cfg.act, cfg.dtype, ffn_out, ws)
+    b_combine = P.bind_combine(ctx, ret, s2r, w, None, y)
+
+    def cur():
+        return torch.cuda.current_stream().cuda_stream
+
     def step():
-        P.moe_route(ctx, x, wg, bias, idx, w)
-        P.moe_traffic(ctx, idx, e2g, expert_count, dest_count, n_dropped)
-        P.moe_dispatch(ctx, x, idx, e2g, dest_order, send_buf, s2r, r2s, seg_offset, seg_expert)
+        st = cur()
+        b_route(st)
+        b_traffic(st)
+        b_dispatch(st)
         for (r0, lo, hi) in self_spans:                      # loop-back part of the first all-to-all
             recv[r0:r0 + hi - lo].copy_(send_buf[lo:hi], non_blocking=True)
-        P.moe_expert_ffn(recv, R, ffn_off, ffn_exp, len(exp), table, H, F, cfg.act, cfg.dtype, ffn_out, ws)
+        b_ffn(st)
         for (r0, lo, hi) in self_spans:                      # loop-back part of the second all-to-all
             ret[lo:hi].copy_(ffn_out[r0:r0 + hi - lo], non_blocking=True)
-        P.moe_combine(ctx, ret, s2r, w, None, y)
+        b_combine(st)
 
-    stages = {
-        "route": lambda: P.moe_route(ctx, x, wg, bias, idx, w),
-        "traffic": lambda: P.moe_traffic(ctx, idx, e2g, expert_count, dest_count, n_dropped),
-        "dispatch": lambda: P.moe_dispatch(ctx, x, idx, e2g, dest_order, send_buf, s2r, r2s, seg_offset, seg_expert),
-        "expert_ffn": lambda: P.moe_expert_ffn(recv, R, ffn_off, ffn_exp, len(exp), table, H, F, cfg.act, cfg.dtype,
-                                               ffn_out, ws),
-        "combine": lambda: P.moe_combine(ctx, ret, s2r, w, None, y),
-    }
+    stages = {"route": lambda: b_route(cur()), "traffic": lambda: b_traffic(cur()), "dispatch": lambda: b_dispatch(cur()),
+              "expert_ffn": lambda: b_ffn(cur()), "combine": lambda: b_combine(cur())}
     ffn_timed = lambda: P.moe_expert_ffn_timed(recv, R, ffn_off, ffn_exp, len(exp), table, H, F, cfg.act, cfg.dtype,
                                                ffn_out, ws)
     n_kept = int(so[-1])
-    return dict(step=step, stages=stages, ffn_timed=ffn_timed, R=R, g=g, n_kept=n_kept, inp=inp,
+    return dict(step=step, stages=stages, ffn_timed=ffn_timed, R=R, g=g, n_kept=n_kept, inp=inp, y=y,
                 keep=(ctx, x, wg, bias, experts, table, recv, ret, ffn_out, ws, send_buf))
 
 
-def time_events(torch, fn, reps):
-    """Average milliseconds of fn() over `reps` back-to-back launches, by events on the launch stream."""
+def capture(torch, fn, reps=1):
+    """Record `reps` calls of fn into a HIP graph on a side stream (default priority)."""
+    g = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        fn()                                                 # one eager call on the capture stream first
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g, stream=s):
+        for _ in range(reps):
+            fn()
+    return g
+
+
+def time_graph(torch, g, launches, per_launch):
+    """Average milliseconds per recorded call: events around `launches` replays on the current stream."""
+    g.replay()
+    torch.cuda.synchronize()
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     a.record()
-    for _ in range(reps):
-        fn()
+    for _ in range(launches):
+        g.replay()
     b.record()
     b.synchronize()
-    return a.elapsed_time(b) / reps
+    return a.elapsed_time(b) / (launches * per_launch)
 
 
 def cpu_baseline(cfg, wl, W):
@@ -177,6 +197,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c2_mixtral")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true", help="launch every kernel from Python instead of replaying a HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU's share of the layer; there is no multi-GPU path in this build "
@@ -195,21 +216,42 @@ def main():
     wl = build_workload(cfg, torch, P, W)
     step = wl["step"]
 
+    # The step is recorded once into a HIP graph (no memset nodes: the library clears nothing with
+    # hipMemsetAsync) and replayed; replays are checked against the eager result before timing.
+    step()
+    torch.cuda.synchronize()
+    y_eager = wl["y"].clone()
+    use_graph = not args.no_graph
+    if use_graph:
+        g_step = capture(torch, step)
+        for _ in range(3):
+            wl["y"].zero_()
+            g_step.replay()
+            torch.cuda.synchronize()
+            if not torch.equal(wl["y"], y_eager):
+                print("graph replay differs from the eager step", file=sys.stderr)
+                sys.exit(3)
+        run_step = g_step.replay
+    else:
+        run_step = step
     for _ in range(args.warmup):
-        step()
+        run_step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     a.record()
     for _ in range(args.steps):
-        step()
+        run_step()
     b.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
     ms_per_step = a.elapsed_time(b) / args.steps
 
-    stage_ms = {name: time_events(torch, fn, max(3, args.steps // 2)) for name, fn in wl["stages"].items()}
     reps = max(3, args.steps // 2)
+    stage_ms = {}
+    for name, fn in wl["stages"].items():                   # GPU time of each stage: 10 calls per graph replay
+        per = 10 if name != "expert_ffn" else 1
+        stage_ms[name] = time_graph(torch, capture(torch, fn, per), reps, per)
     gemm_ms = np.mean([wl["ffn_timed"]() for _ in range(reps)], axis=0)   # tile map, GEMM1 (+act), GEMM2
 
     R, T, k, H, F, b_el = wl["R"], cfg.T, cfg.k, cfg.H, cfg.F, (2 if cfg.dtype == "bf16" else 4)
@@ -226,7 +268,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "T": T, "H": H, "F": F, "E": cfg.E, "k": k, "G": cfg.G,
                    "received_rows": R, "gpu_under_test": wl["g"], "act": cfg.act},
-        "wall_ms_per_step": wall_ms,
+        "wall_ms_per_step": wall_ms, "launch": "hip graph replay" if use_graph else "eager",
         "stage_ms": {n: round(v, 4) for n, v in stage_ms.items()},
         "stage_rate": {
             "route_GBps": bytes_route / (stage_ms["route"] * 1e-3) / 1e9,

@@ -73,11 +73,19 @@ typedef struct {
     int32_t capacity; /* rows kept per expert on this source GPU; 0 = unlimited */
 } moe_shape;
 
-/* Opaque per-shape context.  Owns only small device scratch for the counting
- * scans (a few KB per 1024 slots), allocated once in moe_ctx_create on the
- * current device.  A context must not be used by two streams at once. */
+/* Opaque per-shape context.  Owns small device scratch for the counting sort
+ * (4 bytes per slot plus a few KB), allocated once in moe_ctx_create on the
+ * current device.  A context must not be used by two streams at once.
+ *
+ * The context caches the slot ranks computed by moe_traffic: a following
+ * moe_dispatch that is given the SAME topk_idx pointer reuses them and is a single
+ * kernel.  moe_route marks the cache stale (it rewrites the indices), and
+ * moe_dispatch recomputes the ranks itself whenever the cache is stale or was made
+ * for another pointer.  A caller that rewrites topk_idx in place by other means
+ * must call moe_ctx_invalidate (or moe_traffic) before the next moe_dispatch. */
 typedef struct moe_ctx moe_ctx;
 int moe_ctx_create(moe_ctx** out, const moe_shape* shape);
+int moe_ctx_invalidate(moe_ctx* ctx);
 int moe_ctx_destroy(moe_ctx* ctx); /* NULL is accepted */
 
 /* Gate (Sec. 2.1): logit[t,e] = sum_h x[t,h]*Wg[e,h] (+ gate_bias[e]); the k

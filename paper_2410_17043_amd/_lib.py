@@ -29,6 +29,7 @@ SIGNATURES = {
     "moe_last_error": (C.c_char_p, []),
     "moe_ctx_create": (C.c_int, [C.POINTER(_vp), C.POINTER(moe_shape)]),
     "moe_ctx_destroy": (C.c_int, [_vp]),
+    "moe_ctx_invalidate": (C.c_int, [_vp]),
     "moe_route": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "moe_traffic": (C.c_int, [_vp, _vp, C.POINTER(_i32), _vp, _vp, _vp, _vp]),
     "moe_dispatch": (C.c_int, [_vp, _vp, _vp, C.POINTER(_i32), C.POINTER(_i32), _vp, _vp, _vp, _vp, _vp, _vp]),

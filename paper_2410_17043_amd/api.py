@@ -59,6 +59,10 @@ class MoeCtx:
         self.handle = C.c_void_p()
         _check("moe_ctx_create", self.lib.moe_ctx_create(C.byref(self.handle), C.byref(self.shape)))
 
+    def invalidate(self):
+        """Forget cached slot ranks (needed only after rewriting topk_idx in place outside the library)."""
+        _check("moe_ctx_invalidate", self.lib.moe_ctx_invalidate(self.handle))
+
     def close(self):
         if self.handle:
             self.lib.moe_ctx_destroy(self.handle)
@@ -69,6 +73,62 @@ class MoeCtx:
             self.close()
         except Exception:
             pass
+
+
+class Bound:
+    """A C call with its arguments marshalled once; calling it only enqueues the work.
+
+    Keeps the Python objects that own the argument memory alive.  The stream is the one
+    that was current when the call was bound, unless `stream` is given at call time.
+    """
+
+    __slots__ = ("fn", "name", "args", "keep", "stream_pos")
+
+    def __init__(self, fn, name, args, keep, stream_pos):
+        self.fn, self.name, self.args, self.keep, self.stream_pos = fn, name, list(args), keep, stream_pos
+
+    def __call__(self, stream=None):
+        if stream is not None:
+            self.args[self.stream_pos] = C.c_void_p(stream)
+        rc = self.fn(*self.args)
+        if rc != 0:
+            raise MoeError(self.name, rc)
+
+
+def bind_route(ctx, x, w_gate, gate_bias, topk_idx, topk_w):
+    return Bound(ctx.lib.moe_route, "moe_route", (ctx.handle, _ptr(x), _ptr(w_gate), _ptr(gate_bias), _ptr(topk_idx),
+                                                  _ptr(topk_w), _stream()), (ctx, x, w_gate, gate_bias, topk_idx, topk_w), 6)
+
+
+def bind_traffic(ctx, topk_idx, expert_to_gpu, expert_count, dest_count, n_dropped):
+    a, e2g = _i32_array(expert_to_gpu)
+    return Bound(ctx.lib.moe_traffic, "moe_traffic", (ctx.handle, _ptr(topk_idx), e2g, _ptr(expert_count),
+                                                      _ptr(dest_count), _ptr(n_dropped), _stream()),
+                 (ctx, topk_idx, a, expert_count, dest_count, n_dropped), 6)
+
+
+def bind_dispatch(ctx, x, topk_idx, expert_to_gpu, dest_order, send_buf, slot_to_row, row_to_slot, seg_offset,
+                  seg_expert):
+    a, e2g = _i32_array(expert_to_gpu)
+    b, order = _i32_array(dest_order)
+    return Bound(ctx.lib.moe_dispatch, "moe_dispatch",
+                 (ctx.handle, _ptr(x), _ptr(topk_idx), e2g, order, _ptr(send_buf), _ptr(slot_to_row), _ptr(row_to_slot),
+                  _ptr(seg_offset), _ptr(seg_expert), _stream()),
+                 (ctx, x, topk_idx, a, b, send_buf, slot_to_row, row_to_slot, seg_offset, seg_expert), 10)
+
+
+def bind_expert_ffn(recv, R, seg_offset, seg_expert, nseg, experts, H, F, act, dtype, out, workspace):
+    tab = experts if isinstance(experts, C.Array) else expert_table(experts)
+    return Bound(_lib.load().moe_expert_ffn, "moe_expert_ffn",
+                 (_ptr(recv), R, _ptr(seg_offset), _ptr(seg_expert), nseg, tab, len(tab), H, F, act, _DT[dtype],
+                  _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
+                 (recv, seg_offset, seg_expert, tab, experts, out, workspace), 14)
+
+
+def bind_combine(ctx, ret, slot_to_row, topk_w, shared_out, y):
+    return Bound(ctx.lib.moe_combine, "moe_combine", (ctx.handle, _ptr(ret), _ptr(slot_to_row), _ptr(topk_w),
+                                                      _ptr(shared_out), _ptr(y), _stream()),
+                 (ctx, ret, slot_to_row, topk_w, shared_out, y), 6)
 
 
 def moe_route(ctx, x, w_gate, gate_bias, topk_idx, topk_w):

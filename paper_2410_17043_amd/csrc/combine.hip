@@ -54,30 +54,40 @@ __global__ __launch_bounds__(256) void combine_kernel(const u32x4* __restrict__ 
         rows[j] = (j < k) ? slot_to_row[(size_t)t * k + j] : -1;
         w[j] = (j < k) ? topk_w[(size_t)t * k + j] : 0.f;
     }
-    for (int c = lane; c < row16; c += 64) {
-        u32x4 q[KM];
+    // two 16-byte chunks per lane per trip: 2k independent row loads in flight before the first use
+    for (int c0 = lane; c0 < row16; c0 += 128) {
+        u32x4 q[2][KM];
 #pragma unroll
-        for (int j = 0; j < KM; ++j)
-            if (rows[j] >= 0) q[j] = __builtin_nontemporal_load(ret + (size_t)rows[j] * row16 + c);
-        float acc[V];
+        for (int u = 0; u < 2; ++u) {
+            const int c = c0 + 64 * u;
 #pragma unroll
-        for (int v = 0; v < V; ++v) acc[v] = 0.f;
+            for (int j = 0; j < KM; ++j)
+                if (c < row16 && rows[j] >= 0) q[u][j] = __builtin_nontemporal_load(ret + (size_t)rows[j] * row16 + c);
+        }
 #pragma unroll
-        for (int j = 0; j < KM; ++j) {
-            if (rows[j] >= 0) {
-                float f[V];
-                Pack<DT>::unpack(q[j], f);
+        for (int u = 0; u < 2; ++u) {
+            const int c = c0 + 64 * u;
+            if (c >= row16) continue;
+            float acc[V];
 #pragma unroll
-                for (int v = 0; v < V; ++v) acc[v] = fmaf(w[j], f[v], acc[v]);
+            for (int v = 0; v < V; ++v) acc[v] = 0.f;
+#pragma unroll
+            for (int j = 0; j < KM; ++j) {
+                if (rows[j] >= 0) {
+                    float f[V];
+                    Pack<DT>::unpack(q[u][j], f);
+#pragma unroll
+                    for (int v = 0; v < V; ++v) acc[v] = fmaf(w[j], f[v], acc[v]);
+                }
             }
-        }
-        if (shared_out) {
-            float f[V];
-            Pack<DT>::unpack(shared_out[(size_t)t * row16 + c], f);
+            if (shared_out) {
+                float f[V];
+                Pack<DT>::unpack(shared_out[(size_t)t * row16 + c], f);
 #pragma unroll
-            for (int v = 0; v < V; ++v) acc[v] += f[v];
+                for (int v = 0; v < V; ++v) acc[v] += f[v];
+            }
+            __builtin_nontemporal_store(Pack<DT>::pack(acc), y + (size_t)t * row16 + c);
         }
-        __builtin_nontemporal_store(Pack<DT>::pack(acc), y + (size_t)t * row16 + c);
     }
 }
 

@@ -33,7 +33,9 @@ struct moe_ctx {
     int32_t n_slots;      // T * k
     int32_t n_blocks;     // ceil(n_slots / MOE_SLOTS_PER_BLOCK)
     int32_t* block_hist;  // device [n_blocks][E]: slots per expert in each block, later its exclusive prefix
-    int32_t* seg_start;   // device [E]: first send row of each expert
+    int32_t* raw_count;   // device [E]: slots per expert before the capacity rule
+    int32_t* slot_rank;   // device [n_slots]: rank of a slot among the slots of its expert (-1: index out of range)
+    const void* rank_src; // host: the topk_idx pointer slot_rank was computed from, NULL if stale
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // 16-byte load/store unit

@@ -1,16 +1,23 @@
 // Traffic row (Sec. 4: d_gj) and the buffer layer that fills the send buffer in
 // the planned transmission order (Sec. 3, "Communication scheduling").
 //
-// Both are one stable counting sort of the T*k slots by expert, done without
-// atomics so the permutation is the same on every run:
-//   1. count_kernel   per block of 1024 consecutive slots: slots per expert
-//                     (wave ballots, summed through LDS)          -> block_hist
-//   2. scan_kernel    one block: exclusive prefix over blocks per expert, the
-//                     capacity rule, the traffic row, segment offsets in send order
-//   3. rank_kernel    same ballots again: rank of every slot among the slots of
-//                     its expert -> slot_to_row / row_to_slot
-//   4. copy_kernel    one wave per token: the row is read once and written to the
-//                     send rows of its kept slots (16-byte lanes, 1 KB per wave access)
+// Both rest on one stable counting sort of the T*k slots by expert, done without
+// atomics so the permutation is the same on every run.
+//
+// Rank pass (moe_traffic, or moe_dispatch when no fresh ranks are cached in the context):
+//   every slot gets its rank among the slots of its expert, in slot order, plus the
+//   per-expert totals.  Up to 16384 slots this is ONE block of 16 waves (a launch costs
+//   more than the whole count at that size); beyond, three kernels:
+//     count_kernel   per block of 1024 consecutive slots: slots per expert (wave ballots)
+//     scan_kernel    one block: exclusive prefix over blocks per expert
+//     rank_kernel    the same ballots again: block prefix + rank inside the block
+//   The capacity rule, the traffic row and the drop count follow from the totals.
+//
+// Scatter (moe_dispatch): one kernel, one wave per token.  Every block first turns the
+// per-expert totals into segment starts for the requested destination order (a 256-wide
+// prefix sum), then each wave computes the send rows of its token's slots from the cached
+// ranks, writes slot_to_row / row_to_slot, reads the token row once and writes it to the
+// rows of its kept slots (16-byte lanes, 1 KB per wave access, streaming loads/stores).
 #include "common.h"
 
 namespace {
@@ -18,12 +25,13 @@ namespace {
 struct SegMap {                       // built on the host from expert_to_gpu and dest_order
     int16_t seg_expert[MOE_MAX_E];    // expert at each position of the send order
     uint8_t expert_gpu[MOE_MAX_E];    // destination GPU of each expert
+    uint8_t expert_pos[MOE_MAX_E];    // position of each expert in the send order (inverse of seg_expert)
 };
 
 constexpr int kChunks = MOE_SLOTS_PER_BLOCK / 64;   // 16 chunks of 64 slots per block, in slot order
 
-// cnt[chunk][e] for this block's 16 chunks; returns this lane's rank inside its chunk
-// among the lanes with the same expert (per round, in lane_rank[r]).
+// cnt[chunk][e] for this block's 16 chunks; lane_rank[r] = rank of this lane's slot inside its
+// chunk among the lanes with the same expert.
 template <bool WANT_RANK>
 __device__ __forceinline__ void block_chunk_counts(const int32_t* __restrict__ idx, int n_slots, int E, int* cnt,
                                                    int (&my_e)[4], int (&lane_rank)[4]) {
@@ -60,12 +68,34 @@ __global__ __launch_bounds__(256) void count_kernel(const int32_t* __restrict__ 
     }
 }
 
+// Traffic row, drop count and per-expert kept counts from the raw totals (first E threads of a block).
+__device__ __forceinline__ void traffic_outputs(const int* raw, int* kept, int E, int G, int capacity, const SegMap& map,
+                                                int32_t* __restrict__ expert_count, int32_t* __restrict__ dest_count,
+                                                int32_t* __restrict__ n_dropped) {
+    const int e = threadIdx.x;
+    if (e < E) {
+        kept[e] = (capacity > 0 && raw[e] > capacity) ? capacity : raw[e];
+        if (expert_count) expert_count[e] = kept[e];
+    }
+    __syncthreads();
+    if (dest_count && e < G) {
+        int s = 0;
+        for (int i = 0; i < E; ++i)
+            if (map.expert_gpu[i] == e) s += kept[i];
+        dest_count[e] = s;
+    }
+    if (n_dropped && e == 0) {
+        int drop = 0;
+        for (int i = 0; i < E; ++i) drop += raw[i] - kept[i];
+        *n_dropped = drop;
+    }
+}
+
 // One block of 256 threads.  Thread e walks the blocks of expert e.
 __global__ __launch_bounds__(256) void scan_kernel(int32_t* __restrict__ block_hist, int n_blocks, int E, int G,
-                                                   int capacity, SegMap map, int32_t* __restrict__ seg_start,
+                                                   int capacity, SegMap map, int32_t* __restrict__ raw_count,
                                                    int32_t* __restrict__ expert_count, int32_t* __restrict__ dest_count,
-                                                   int32_t* __restrict__ n_dropped, int32_t* __restrict__ seg_offset,
-                                                   int32_t* __restrict__ seg_expert) {
+                                                   int32_t* __restrict__ n_dropped) {
     __shared__ int kept[MOE_MAX_E];
     __shared__ int raw[MOE_MAX_E];
     const int e = threadIdx.x;
@@ -77,35 +107,15 @@ __global__ __launch_bounds__(256) void scan_kernel(int32_t* __restrict__ block_h
             run += c;
         }
         raw[e] = run;
-        kept[e] = (capacity > 0 && run > capacity) ? capacity : run;
-        if (expert_count) expert_count[e] = kept[e];
+        raw_count[e] = run;
     }
     __syncthreads();
-    if (dest_count && e < G) {
-        int s = 0;
-        for (int i = 0; i < E; ++i)
-            if (map.expert_gpu[i] == e) s += kept[i];
-        dest_count[e] = s;
-    }
-    if (e == 0) {
-        int run = 0, drop = 0;
-        for (int p = 0; p < E; ++p) {
-            const int ex = map.seg_expert[p];
-            if (seg_offset) seg_offset[p] = run;
-            if (seg_expert) seg_expert[p] = ex;
-            if (seg_start) seg_start[ex] = run;
-            run += kept[ex];
-            drop += raw[ex] - kept[ex];
-        }
-        if (seg_offset) seg_offset[E] = run;
-        if (n_dropped) *n_dropped = drop;
-    }
+    traffic_outputs(raw, kept, E, G, capacity, map, expert_count, dest_count, n_dropped);
 }
 
-__global__ __launch_bounds__(256) void rank_kernel(const int32_t* __restrict__ idx, int n_slots, int E, int capacity,
+__global__ __launch_bounds__(256) void rank_kernel(const int32_t* __restrict__ idx, int n_slots, int E,
                                                    const int32_t* __restrict__ block_base,
-                                                   const int32_t* __restrict__ seg_start,
-                                                   int32_t* __restrict__ slot_to_row, int32_t* __restrict__ row_to_slot) {
+                                                   int32_t* __restrict__ slot_rank) {
     extern __shared__ int cnt[];      // [16][E], turned into an exclusive prefix over chunks
     int my_e[4], lane_rank[4];
     block_chunk_counts<true>(idx, n_slots, E, cnt, my_e, lane_rank);
@@ -127,40 +137,205 @@ __global__ __launch_bounds__(256) void rank_kernel(const int32_t* __restrict__ i
         const int s = base + r * 64 + lane;
         if (s < n_slots) {
             const int e = my_e[r];
-            int row = -1;
-            if (e >= 0 && e < E) {                      // an index outside [0, E) is treated as a dropped slot
-                const int rank = cnt[(wave * 4 + r) * E + e] + lane_rank[r];
-                if (capacity <= 0 || rank < capacity) {
-                    row = seg_start[e] + rank;
-                    row_to_slot[row] = s;
-                }
-            }
-            slot_to_row[s] = row;
+            slot_rank[s] = (e >= 0 && e < E) ? cnt[(wave * 4 + r) * E + e] + lane_rank[r] : -1;
         }
     }
 }
 
+constexpr int kSmallMaxSlots = 16384;
+constexpr int kSmallRounds = kSmallMaxSlots / (16 * 64);     // rounds of 64 slots per wave
+
+// The whole rank pass in one block of 1024 threads.  Wave w owns the slots [w*spw, (w+1)*spw),
+// round by round; per round the lanes are grouped by expert with ballots (one ballot per distinct
+// expert present) and the wave's running per-expert counts live in registers (lane e % 64 holds
+// expert e), so a round costs a few register operations per distinct expert.
+__global__ __launch_bounds__(1024) void small_rank_kernel(const int32_t* __restrict__ idx, int n_slots, int E, int G,
+                                                          int capacity, SegMap map, int32_t* __restrict__ raw_count,
+                                                          int32_t* __restrict__ slot_rank,
+                                                          int32_t* __restrict__ expert_count,
+                                                          int32_t* __restrict__ dest_count,
+                                                          int32_t* __restrict__ n_dropped) {
+    __shared__ int wave_cnt[16][MOE_MAX_E];  // per wave: slots per expert, later the wave's base rank
+    __shared__ int kept[MOE_MAX_E], raw[MOE_MAX_E];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int rounds = (n_slots + 1023) / 1024;            // per wave
+    const int base = wave * rounds * 64;
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    int my_e[kSmallRounds], my_rank[kSmallRounds];
+#pragma unroll
+    for (int r = 0; r < kSmallRounds; ++r) {               // all index loads first
+        const int s = base + r * 64 + lane;
+        int e = (r < rounds && s < n_slots) ? idx[s] : -1;
+        my_e[r] = (e < E) ? e : -1;                         // out of range: no rank
+        my_rank[r] = -1;
+    }
+    int run[MOE_MAX_E / 64] = {0, 0, 0, 0};                // lane l: counts of experts l, l+64, l+128, l+192
+    if (E <= 16) {
+        // few experts: one ballot per (expert, round); the running count is wave-uniform
+        for (int e = 0; e < E; ++e) {
+            int cnt = 0;
+#pragma unroll
+            for (int r = 0; r < kSmallRounds; ++r) {
+                if (r < rounds) {
+                    const unsigned long long m = __ballot(my_e[r] == e);
+                    if (my_e[r] == e) my_rank[r] = cnt + __popcll(m & lt);
+                    cnt += __popcll(m);
+                }
+            }
+            if (lane == e) run[0] = cnt;
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < kSmallRounds; ++r) {
+            if (r < rounds) {
+                const int e = my_e[r];
+                unsigned long long todo = __ballot(e >= 0);
+                while (todo) {                              // one trip per distinct expert in this round
+                    const int leader = __builtin_amdgcn_readfirstlane(__ffsll((long long)todo) - 1);
+                    const int cur = __builtin_amdgcn_readlane(e, leader);
+                    const unsigned long long m = __ballot(e == cur);
+                    const int slot = cur >> 6;              // wave-uniform
+                    const int holder = (slot == 0) ? run[0] : (slot == 1) ? run[1] : (slot == 2) ? run[2] : run[3];
+                    const int before = __builtin_amdgcn_readlane(holder, cur & 63);
+                    if (e == cur) my_rank[r] = before + __popcll(m & lt);
+                    if (lane == (cur & 63)) {
+                        const int add = __popcll(m);
+                        if (slot == 0) run[0] += add; else if (slot == 1) run[1] += add; else if (slot == 2) run[2] += add; else run[3] += add;
+                    }
+                    todo &= ~m;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < MOE_MAX_E / 64; ++i)
+        if (lane + 64 * i < E) wave_cnt[wave][lane + 64 * i] = run[i];
+    __syncthreads();
+    if (threadIdx.x < E) {                                 // exclusive scan over the 16 waves
+        const int e = threadIdx.x;
+        int acc = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            const int c = wave_cnt[w][e];
+            wave_cnt[w][e] = acc;
+            acc += c;
+        }
+        raw[e] = acc;
+        raw_count[e] = acc;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < kSmallRounds; ++r) {
+        const int s = base + r * 64 + lane;
+        if (r < rounds && s < n_slots) slot_rank[s] = (my_e[r] >= 0) ? wave_cnt[wave][my_e[r]] + my_rank[r] : -1;
+    }
+    traffic_outputs(raw, kept, E, G, capacity, map, expert_count, dest_count, n_dropped);
+}
+
 // One wave per token.  row16 = 16-byte units per row.
 template <int K>
-__global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ x, const int32_t* __restrict__ slot_to_row,
-                                                   int T, int k_rt, int row16, u32x4* __restrict__ send_buf) {
-    const int lane = threadIdx.x & 63;
-    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (t >= T) return;
+__global__ __launch_bounds__(256) void scatter_kernel(const u32x4* __restrict__ x, const int32_t* __restrict__ idx,
+                                                      const int32_t* __restrict__ slot_rank,
+                                                      const int32_t* __restrict__ raw_count, int T, int k_rt, int E,
+                                                      int capacity, SegMap map, int row16, u32x4* __restrict__ send_buf,
+                                                      int32_t* __restrict__ slot_to_row, int32_t* __restrict__ row_to_slot,
+                                                      int32_t* __restrict__ seg_offset, int32_t* __restrict__ seg_expert) {
+    __shared__ int seg_first[MOE_MAX_E];   // first send row of each expert
+    __shared__ int wave_sum[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int t = blockIdx.x * 4 + wave;
     const int k = (K > 0) ? K : k_rt;
-    int rows[(K > 0) ? K : MOE_MAX_K];
+    const bool live = t < T;
+    const u32x4* src = x + (size_t)(live ? t : 0) * row16;
+    // the first 4 KB of the row are requested before anything else: they do not depend on the ranks
+    u32x4 v[4];
 #pragma unroll
-    for (int j = 0; j < ((K > 0) ? K : MOE_MAX_K); ++j) rows[j] = (j < k) ? slot_to_row[(size_t)t * k + j] : -1;
-    const u32x4* src = x + (size_t)t * row16;
+    for (int u = 0; u < 4; ++u) {
+        const int c = u * 64 + lane;
+        if (live && c < row16) v[u] = __builtin_nontemporal_load(src + c);
+    }
+    // Segment starts in send order.  Up to 64 experts every wave does the prefix sum for itself in
+    // registers (lane p = position p; no barrier, no LDS); beyond, the block shares one through LDS.
+    int excl_reg = 0;                                       // E <= 64: start of the segment at position `lane`
+    if (E <= 64) {
+        const int ex = (lane < E) ? map.seg_expert[lane] : 0;
+        int cnt = (lane < E) ? raw_count[ex] : 0;
+        if (capacity > 0 && cnt > capacity) cnt = capacity;
+        int incl = cnt;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int up = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += up;
+        }
+        excl_reg = incl - cnt;
+        if (blockIdx.x == 0 && wave == 0 && lane < E) {
+            seg_offset[lane] = excl_reg;
+            seg_expert[lane] = ex;
+            if (lane == E - 1) seg_offset[E] = incl;
+        }
+    } else {
+        const int p = threadIdx.x;
+        const int ex = (p < E) ? map.seg_expert[p] : 0;
+        int cnt = (p < E) ? raw_count[ex] : 0;
+        if (capacity > 0 && cnt > capacity) cnt = capacity;
+        int incl = cnt;                                     // inclusive scan inside the wave
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int up = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += up;
+        }
+        if (lane == 63) wave_sum[wave] = incl;
+        __syncthreads();
+        int before = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w)
+            if (w < wave) before += wave_sum[w];
+        const int excl = before + incl - cnt;
+        if (p < E) {
+            seg_first[ex] = excl;
+            if (blockIdx.x == 0) {
+                seg_offset[p] = excl;
+                seg_expert[p] = ex;
+                if (p == E - 1) seg_offset[E] = excl + cnt;
+            }
+        }
+        __syncthreads();
+    }
+    if (!live) return;
+    // send rows of this token's slots: lane j < k works out slot j, then all lanes learn the k rows
+    int my_row = -1, my_e = 0, my_rank = 0;
+    bool kept_slot = false;
+    if (lane < k) {
+        const int s = t * k + lane;
+        const int e = idx[s], rank = slot_rank[s];
+        kept_slot = e >= 0 && e < E && rank >= 0 && (capacity <= 0 || rank < capacity);
+        my_e = kept_slot ? e : 0;
+        my_rank = rank;
+    }
+    // position of an expert in the send order: map.expert_pos is the inverse of map.seg_expert
+    const int first = (E <= 64) ? __shfl(excl_reg, map.expert_pos[my_e], 64) : seg_first[my_e];
+    if (lane < k) {
+        const int s = t * k + lane;
+        if (kept_slot) {
+            my_row = first + my_rank;
+            row_to_slot[my_row] = s;
+        }
+        slot_to_row[s] = my_row;
+    }
+    constexpr int KM = (K > 0) ? K : MOE_MAX_K;
+    int rows[KM];
+#pragma unroll
+    for (int j = 0; j < KM; ++j) rows[j] = (j < k) ? __shfl(my_row, j, 64) : -1;
     for (int c0 = 0; c0 < row16; c0 += 256) {
-        u32x4 v[4];
+        if (c0 > 0) {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int c = c0 + u * 64 + lane;
-            if (c < row16) v[u] = __builtin_nontemporal_load(src + c);
+            for (int u = 0; u < 4; ++u) {
+                const int c = c0 + u * 64 + lane;
+                if (c < row16) v[u] = __builtin_nontemporal_load(src + c);
+            }
         }
 #pragma unroll
-        for (int j = 0; j < ((K > 0) ? K : MOE_MAX_K); ++j) {
+        for (int j = 0; j < KM; ++j) {
             if (rows[j] >= 0) {
                 u32x4* dst = send_buf + (size_t)rows[j] * row16;
 #pragma unroll
@@ -186,20 +361,34 @@ int build_segmap(const moe_shape& s, const int32_t* expert_to_gpu, const int32_t
         if (d < 0 || d >= s.G || seen[d]) return moe_set_error(MOE_ESHAPE, "dest_order is not a permutation of 0..%d", s.G - 1);
         seen[d] = true;
         for (int e = 0; e < s.E; ++e)
-            if (expert_to_gpu[e] == d) m->seg_expert[p++] = (int16_t)e;
+            if (expert_to_gpu[e] == d) {
+                m->expert_pos[e] = (uint8_t)p;
+                m->seg_expert[p++] = (int16_t)e;
+            }
     }
     return MOE_OK;
 }
 
-int launch_count_scan(moe_ctx* c, const int32_t* idx, const SegMap& map, int32_t* expert_count, int32_t* dest_count,
-                      int32_t* n_dropped, int32_t* seg_offset, int32_t* seg_expert, hipStream_t st) {
+// Rank pass; the three count outputs may be NULL.
+int launch_rank_pass(moe_ctx* c, const int32_t* idx, const SegMap& map, int32_t* expert_count, int32_t* dest_count,
+                     int32_t* n_dropped, hipStream_t st) {
     const moe_shape& s = c->s;
-    const size_t lds = (size_t)kChunks * s.E * sizeof(int);
-    hipLaunchKernelGGL(count_kernel, dim3(c->n_blocks), dim3(256), lds, st, idx, c->n_slots, s.E, c->block_hist);
-    MOE_LAUNCH_CHECK("count_kernel");
-    hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(256), 0, st, c->block_hist, c->n_blocks, s.E, s.G, s.capacity, map,
-                       c->seg_start, expert_count, dest_count, n_dropped, seg_offset, seg_expert);
-    MOE_LAUNCH_CHECK("scan_kernel");
+    if (c->n_slots <= kSmallMaxSlots) {
+        hipLaunchKernelGGL(small_rank_kernel, dim3(1), dim3(1024), 0, st, idx, c->n_slots, s.E, s.G, s.capacity, map,
+                           c->raw_count, c->slot_rank, expert_count, dest_count, n_dropped);
+        MOE_LAUNCH_CHECK("small_rank_kernel");
+    } else {
+        const size_t lds = (size_t)kChunks * s.E * sizeof(int);
+        hipLaunchKernelGGL(count_kernel, dim3(c->n_blocks), dim3(256), lds, st, idx, c->n_slots, s.E, c->block_hist);
+        MOE_LAUNCH_CHECK("count_kernel");
+        hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(256), 0, st, c->block_hist, c->n_blocks, s.E, s.G, s.capacity, map,
+                           c->raw_count, expert_count, dest_count, n_dropped);
+        MOE_LAUNCH_CHECK("scan_kernel");
+        hipLaunchKernelGGL(rank_kernel, dim3(c->n_blocks), dim3(256), lds, st, idx, c->n_slots, s.E, c->block_hist,
+                           c->slot_rank);
+        MOE_LAUNCH_CHECK("rank_kernel");
+    }
+    c->rank_src = idx;
     return MOE_OK;
 }
 
@@ -212,8 +401,7 @@ extern "C" int moe_traffic(moe_ctx* ctx, const int32_t* topk_idx, const int32_t*
     SegMap map;
     int rc = build_segmap(ctx->s, expert_to_gpu, nullptr, &map);
     if (rc != MOE_OK) return rc;
-    return launch_count_scan(ctx, topk_idx, map, expert_count, dest_count, n_dropped, nullptr, nullptr,
-                             reinterpret_cast<hipStream_t>(stream));
+    return launch_rank_pass(ctx, topk_idx, map, expert_count, dest_count, n_dropped, reinterpret_cast<hipStream_t>(stream));
 }
 
 extern "C" int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* topk_idx, const int32_t* expert_to_gpu,
@@ -228,19 +416,21 @@ extern "C" int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* topk_idx
     int rc = build_segmap(s, expert_to_gpu, dest_order, &map);
     if (rc != MOE_OK) return rc;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    rc = launch_count_scan(ctx, topk_idx, map, nullptr, nullptr, nullptr, seg_offset, seg_expert, st);
-    if (rc != MOE_OK) return rc;
-    const size_t lds = (size_t)kChunks * s.E * sizeof(int);
-    hipLaunchKernelGGL(rank_kernel, dim3(ctx->n_blocks), dim3(256), lds, st, topk_idx, ctx->n_slots, s.E, s.capacity,
-                       ctx->block_hist, ctx->seg_start, slot_to_row, row_to_slot);
-    MOE_LAUNCH_CHECK("rank_kernel");
+    if (ctx->rank_src != topk_idx) {                     // no fresh ranks for these indices: compute them now
+        rc = launch_rank_pass(ctx, topk_idx, map, nullptr, nullptr, nullptr, st);
+        if (rc != MOE_OK) return rc;
+    }
     const int row16 = (int)((int64_t)s.H * elem_size(s.dtype) / 16);
     const dim3 grid((s.T + 3) / 4);
     const u32x4* xs = reinterpret_cast<const u32x4*>(x);
     u32x4* sb = reinterpret_cast<u32x4*>(send_buf);
-    if (s.k == 1) hipLaunchKernelGGL(copy_kernel<1>, grid, dim3(256), 0, st, xs, slot_to_row, s.T, s.k, row16, sb);
-    else if (s.k == 2) hipLaunchKernelGGL(copy_kernel<2>, grid, dim3(256), 0, st, xs, slot_to_row, s.T, s.k, row16, sb);
-    else hipLaunchKernelGGL(copy_kernel<0>, grid, dim3(256), 0, st, xs, slot_to_row, s.T, s.k, row16, sb);
-    MOE_LAUNCH_CHECK("copy_kernel");
+#define MOE_SCATTER(KK)                                                                                          \
+    hipLaunchKernelGGL(scatter_kernel<KK>, grid, dim3(256), 0, st, xs, topk_idx, ctx->slot_rank, ctx->raw_count, s.T, \
+                       s.k, s.E, s.capacity, map, row16, sb, slot_to_row, row_to_slot, seg_offset, seg_expert)
+    if (s.k == 1) MOE_SCATTER(1);
+    else if (s.k == 2) MOE_SCATTER(2);
+    else MOE_SCATTER(0);
+#undef MOE_SCATTER
+    MOE_LAUNCH_CHECK("scatter_kernel");
     return MOE_OK;
 }

@@ -5,13 +5,15 @@
 // the plain fp32 FMA rate on this chip, so there is no faster exact alternative on
 // the vector units.
 //
-// Mapping: one wave owns TT tokens; the 64 lanes split the hidden dimension in
-// 16-byte chunks (coalesced 1 KB per wave per token row).  Each lane keeps
-// TT x ET fp64 partial logits; Wg chunks are read through L1/L2 (all waves read the
-// same few KB).  The cross-lane sum is a halving butterfly (each exchange step
-// hands half of the values to the partner lane), after which lane l holds one
-// finished logit.  Logits go to LDS, then top-k and softmax run wave-parallel with
-// one candidate expert per lane.
+// Mapping: a block of 4 waves owns TT tokens; each wave takes a quarter of the hidden
+// dimension and its 64 lanes split that quarter in 16-byte chunks (coalesced 1 KB per
+// wave per token row), so every token row is read once and enough waves are in flight
+// to cover HBM latency.  Each lane keeps TT x ET fp64 partial logits; Wg chunks are read
+// through L1/L2 (all blocks read the same few KB).  The cross-lane sum is a halving
+// butterfly (each exchange step hands half of the values to the partner lane), after
+// which lane l holds one partial logit; the four waves' partials are added through LDS.
+// Top-k and softmax then run wave-parallel, one token per wave, one candidate expert
+// per lane.
 #include "common.h"
 
 namespace {
@@ -38,29 +40,31 @@ template <> struct Chunk<MOE_F32> {
 };
 
 // Sum v[0..N) over the 64 lanes.  On return lane l holds in v[0] the total of value
-// index (N == 64 ? l : l >> (6 - log2 N)).
-template <int N>
-__device__ __forceinline__ void halving_reduce(double (&v)[N], int lane) {
-    int n = N;
+// index (N == 64 ? l : l >> (6 - log2 N)).  Written as a compile-time recursion so that
+// every array index is a constant and the values stay in registers.
+template <int N, int CUR, int O>
+struct Halving {
+    __device__ static __forceinline__ void run(double (&v)[N], int lane) {
+        if constexpr (O >= 1) {
+            if constexpr (CUR > 1) {
+                constexpr int HALF = CUR / 2;
+                const bool upper = (lane & O) != 0;
 #pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) {
-        if (n > 1) {
-            const bool upper = (lane & o) != 0;
-            const int half = n / 2;
-#pragma unroll
-            for (int i = 0; i < N / 2; ++i) {
-                if (i < half) {
-                    const double send = upper ? v[i] : v[i + half];
-                    const double keep = upper ? v[i + half] : v[i];
-                    v[i] = keep + __shfl_xor(send, o, 64);
+                for (int i = 0; i < HALF; ++i) {
+                    const double send = upper ? v[i] : v[i + HALF];
+                    const double keep = upper ? v[i + HALF] : v[i];
+                    v[i] = keep + __shfl_xor(send, O, 64);
                 }
+                Halving<N, HALF, O / 2>::run(v, lane);
+            } else {
+                v[0] += __shfl_xor(v[0], O, 64);
+                Halving<N, 1, O / 2>::run(v, lane);
             }
-            n = half;
-        } else {
-            v[0] += __shfl_xor(v[0], o, 64);
         }
     }
-}
+};
+template <int N>
+__device__ __forceinline__ void halving_reduce(double (&v)[N], int lane) { Halving<N, N, 32>::run(v, lane); }
 
 template <int DT, int TT, int ET>
 __global__ __launch_bounds__(256) void route_kernel(const void* __restrict__ x, const void* __restrict__ wg,
@@ -69,49 +73,56 @@ __global__ __launch_bounds__(256) void route_kernel(const void* __restrict__ x, 
                                                     float* __restrict__ topk_w) {
     constexpr int V = Chunk<DT>::V;
     constexpr int N = TT * ET;
-    extern __shared__ double zl[];                       // [4 waves][TT][E]
+    extern __shared__ double zl[];                       // [TT][E] logits, then [4 waves][N] partials
+    double* zpart = zl + (size_t)TT * E;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int tok0 = (blockIdx.x * 4 + wave) * TT;
-    if (tok0 >= T) return;                               // whole wave leaves together; no block barrier is used
-    double* z = zl + (size_t)wave * TT * E;
+    const int tok0 = blockIdx.x * TT;
     const int nchunk = H / V;
+    const int cpw = (nchunk + 3) / 4;                    // chunks per wave
+    const int c_lo = wave * cpw, c_hi = min(c_lo + cpw, nchunk);
 
     for (int e0 = 0; e0 < E; e0 += ET) {
         double acc[N];
 #pragma unroll
         for (int i = 0; i < N; ++i) acc[i] = 0.0;
-        for (int c = lane; c < nchunk; c += 64) {
+        for (int c = c_lo + lane; c < c_hi; c += 64) {
             double xv[TT][V];
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
                 const int t = min(tok0 + tt, T - 1);
                 Chunk<DT>::load(x, (size_t)t * nchunk + c, xv[tt]);
             }
+            // experts past E are clamped to the last row: computed, never written out (keeps every
+            // index below a compile-time constant, so the partial logits stay in registers)
 #pragma unroll
             for (int e = 0; e < ET; ++e) {
-                if (e0 + e < E) {
-                    double wv[V];
-                    Chunk<DT>::load(wg, (size_t)(e0 + e) * nchunk + c, wv);
+                double wv[V];
+                Chunk<DT>::load(wg, (size_t)min(e0 + e, E - 1) * nchunk + c, wv);
 #pragma unroll
-                    for (int tt = 0; tt < TT; ++tt)
+                for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-                        for (int v = 0; v < V; ++v) acc[tt * ET + e] = fma(xv[tt][v], wv[v], acc[tt * ET + e]);
-                }
+                    for (int v = 0; v < V; ++v) acc[tt * ET + e] = fma(xv[tt][v], wv[v], acc[tt * ET + e]);
             }
         }
         halving_reduce<N>(acc, lane);
         const int index = (N == 64) ? lane : (lane >> 1);   // N is 32 or 64
-        const int tt = index / ET, e = e0 + index % ET;
-        if ((N == 64 || (lane & 1) == 0) && e < E) z[tt * E + e] = acc[0] + (bias ? (double)bias[e] : 0.0);
+        if (N == 64 || (lane & 1) == 0) zpart[wave * N + index] = acc[0];
+        __syncthreads();
+        if (threadIdx.x < N) {
+            const int tt = threadIdx.x / ET, e = e0 + threadIdx.x % ET;
+            if (e < E)
+                zl[tt * E + e] = ((zpart[threadIdx.x] + zpart[N + threadIdx.x]) +
+                                  (zpart[2 * N + threadIdx.x] + zpart[3 * N + threadIdx.x])) +
+                                 (bias ? (double)bias[e] : 0.0);
+        }
+        __syncthreads();
     }
-    // the logits written by other lanes of this wave must be visible before they are read back
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-    for (int tt = 0; tt < TT; ++tt) {
-        const int t = tok0 + tt;
-        if (t >= T) break;
+    // one token per wave
+    const int tt = wave, t = tok0 + wave;
+    if (tt >= TT || t >= T) return;
+    const double* z = zl;
+    {
         // up to 4 candidate experts per lane: lane, lane + 64, ...
         double cand[MOE_MAX_E / 64];
         bool taken[MOE_MAX_E / 64];
@@ -169,9 +180,8 @@ template <int DT, int TT, int ET>
 int launch_route(const moe_ctx* c, const void* x, const void* wg, const float* bias, int32_t* idx, float* w,
                  hipStream_t st) {
     const moe_shape& s = c->s;
-    const int tokens_per_block = 4 * TT;
-    const int grid = (s.T + tokens_per_block - 1) / tokens_per_block;
-    const size_t lds = (size_t)4 * TT * s.E * sizeof(double);
+    const int grid = (s.T + TT - 1) / TT;
+    const size_t lds = ((size_t)TT * s.E + 4 * TT * ET) * sizeof(double);
     hipLaunchKernelGGL((route_kernel<DT, TT, ET>), dim3(grid), dim3(256), lds, st, x, wg, bias, s.T, s.H, s.E, s.k,
                        s.renorm, idx, w);
     MOE_LAUNCH_CHECK("route_kernel");
@@ -195,6 +205,7 @@ extern "C" int moe_route(moe_ctx* ctx, const void* x, const void* Wg, const floa
     if (!ctx || !x || !Wg || !topk_idx || !topk_w) return moe_set_error(MOE_EINVAL, "moe_route: NULL argument");
     if (!aligned16(x) || !aligned16(Wg)) return moe_set_error(MOE_EALIGN, "moe_route: x and Wg must be 16-byte aligned");
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    ctx->rank_src = nullptr;                             // the indices are about to change: cached slot ranks are stale
     if (ctx->s.dtype == MOE_BF16) return route_dispatch<MOE_BF16>(ctx, x, Wg, gate_bias, topk_idx, topk_w, st);
     return route_dispatch<MOE_F32>(ctx, x, Wg, gate_bias, topk_idx, topk_w, st);
 }

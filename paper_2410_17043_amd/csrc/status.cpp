@@ -51,15 +51,22 @@ extern "C" int moe_ctx_create(moe_ctx** out, const moe_shape* shape) {
     c->n_slots = shape->T * shape->k;
     c->n_blocks = (c->n_slots + MOE_SLOTS_PER_BLOCK - 1) / MOE_SLOTS_PER_BLOCK;
     c->block_hist = nullptr;
-    c->seg_start = nullptr;
-    size_t bytes = ((size_t)c->n_blocks * shape->E + shape->E) * sizeof(int32_t);
+    c->rank_src = nullptr;
+    size_t bytes = ((size_t)c->n_blocks * shape->E + shape->E + (size_t)c->n_slots) * sizeof(int32_t);
     hipError_t e = hipMalloc((void**)&c->block_hist, bytes);
     if (e != hipSuccess) {
         delete c;
         return moe_set_error(e == hipErrorOutOfMemory ? MOE_ENOMEM : MOE_EHIP, "hipMalloc(%zu): %s", bytes, hipGetErrorString(e));
     }
-    c->seg_start = c->block_hist + (size_t)c->n_blocks * shape->E;
+    c->raw_count = c->block_hist + (size_t)c->n_blocks * shape->E;
+    c->slot_rank = c->raw_count + shape->E;
     *out = c;
+    return MOE_OK;
+}
+
+extern "C" int moe_ctx_invalidate(moe_ctx* ctx) {
+    if (!ctx) return moe_set_error(MOE_EINVAL, "moe_ctx_invalidate: ctx is NULL");
+    ctx->rank_src = nullptr;
     return MOE_OK;
 }
 

@@ -23,7 +23,8 @@ def test_every_declared_symbol_is_exported_and_bound():
     names = declared_functions()
     assert {"moe_route", "moe_traffic", "moe_dispatch", "moe_expert_ffn", "moe_combine", "aurora_order",
             "colocate_match", "moe_ctx_create", "moe_ctx_destroy", "moe_ffn_workspace_bytes", "moe_status_str",
-            "moe_last_error", "aurora_schedule_free", "aurora_simulate"} <= set(names)
+            "moe_last_error", "aurora_schedule_free", "aurora_simulate", "moe_ctx_invalidate",
+            "moe_expert_ffn_timed"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
         assert n in _lib.SIGNATURES, n

@@ -89,6 +89,11 @@ DISPATCH_CASES = [
     (small("c3_switch", T=2100, H=64), 7),
     (small("c5_finegrained", T=1111, H=136), 0),
     (small("c5_finegrained", T=700, H=64, E=160, k=9, G=16), 30),
+    # more than 16384 slots: the multi-block counting path
+    (small("c5_finegrained", T=3100, H=64), 0),
+    (small("c3_switch", T=20011, H=32), None),
+    (small("c2_mixtral", T=8193, H=64), 0),               # 16386 slots, just over the single-block limit
+    (small("c2_mixtral", T=8192, H=64), 0),               # 16384 slots, the single-block limit itself
 ]
 
 
@@ -135,6 +140,40 @@ def test_traffic_and_dispatch(H, cfg, cap):
     sh.dispatch(x, e2g, orders[-1])
     torch.cuda.synchronize()
     assert torch.equal(a, sh.slot_to_row)
+
+
+@pytest.mark.parametrize("cfg", [small("c2_mixtral", T=700, H=264), small("c5_finegrained", T=3000, H=64)],
+                         ids=lambda c: c.name)
+def test_dispatch_alone_and_after_in_place_index_rewrite(H, cfg):
+    """moe_dispatch without a preceding moe_traffic, and the stale-cache rules of the context."""
+    inp = W.make_layer_inputs(cfg)
+    e2g = inp["expert_to_gpu"]
+    order = list(np.random.default_rng(3).permutation(cfg.G))
+    idx_a, _, _ = O.route(inp["x"], inp["w_gate"], inp["gate_bias"], cfg.k, cfg.renorm)
+    idx_b = np.ascontiguousarray(idx_a[::-1])                      # a different, still valid, routing
+    x = H.dev(inp["x"], cfg.dtype)
+    sh = H.Share(cfg)
+
+    def check(idx_ref):
+        ref = O.dispatch(inp["x"], idx_ref, e2g, order, cfg.capacity)
+        torch.cuda.synchronize()
+        assert np.array_equal(H.host(sh.slot_to_row), ref["slot_to_row"])
+        assert np.array_equal(H.host(sh.seg_offset), ref["seg_offset"])
+        assert np.array_equal(H.host(sh.send_buf)[:ref["n_rows"]], ref["send_buf"])
+
+    sh.idx.copy_(torch.from_numpy(idx_a))
+    sh.dispatch(x, e2g, order)                                     # fresh context: ranks computed inside
+    check(idx_a)
+    sh.traffic(e2g)                                                # caches ranks for idx_a
+    sh.idx.copy_(torch.from_numpy(idx_b))                          # rewritten in place behind the library's back
+    sh.ctx.invalidate()
+    sh.dispatch(x, e2g, order)
+    check(idx_b)
+    other = sh.idx.clone()                                         # same contents, another pointer: never served from cache
+    other.copy_(torch.from_numpy(idx_a))
+    H.P.moe_dispatch(sh.ctx, x, other, e2g, order, sh.send_buf, sh.slot_to_row, sh.row_to_slot, sh.seg_offset,
+                     sh.seg_expert)
+    check(idx_a)
 
 
 def make_segments(r, R, nseg, n_local):
