@@ -23,6 +23,9 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+# HBM-side bytes per launch of the first FFN GEMM at c2_mixtral from rocprofv3 counters (FETCH_SIZE x 2.0 +
+# WRITE_SIZE x 1.0, see profiles/bench_c2_mixtral_layer_share.md); None once the kernel has changed since.
+GEMM1_TRAFFIC_BYTES = {"c2_mixtral": 4.5551e6 * 1024 * 2.0 + 5.7599e5 * 1024 * 1.0}
 
 
 def build_workload(cfg, torch, P, W):
@@ -102,6 +105,12 @@ def build_workload(cfg, torch, P, W):
     for r0 in range(0, S, chunk):                            # rows returned by other GPUs: seeded N(0,1)
         n = min(chunk, S - r0)
         ret[r0:r0 + n] = to_dev(W.generate.make_rows(cfg, W.generate.S_RET, n, sub=r0 // chunk))
+    # a plain device copy of known size (256 MiB read + 256 MiB written): the reference that the
+    # FETCH_SIZE / WRITE_SIZE hardware counters of a profiled run are scaled by
+    calib_src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+    calib_dst = torch.empty_like(calib_src)
+    calib_dst.copy_(calib_src)
+    del calib_src, calib_dst
     torch.cuda.synchronize()
 
     b_route = P.bind_route(ctx, x, wg, bias, idx, w)
@@ -131,7 +140,10 @@ def build_workload(cfg, torch, P, W):
                                                ffn_out, ws)
     n_kept = int(so[-1])
     return dict(step=step, stages=stages, ffn_timed=ffn_timed, R=R, g=g, n_kept=n_kept, inp=inp, y=y,
-                keep=(ctx, x, wg, bias, experts, table, recv, ret, ffn_out, ws, send_buf))
+                idx=idx, w=w, expert_count=expert_count, dest_count=dest_count, n_dropped=n_dropped,
+                send_buf=send_buf, slot_to_row=s2r, row_to_slot=r2s, seg_offset=seg_offset, seg_expert=seg_expert,
+                recv=recv, ffn_out=ffn_out, ret=ret, ffn_off=off, ffn_exp=exp, local=local, dest_order=dest_order,
+                self_spans=self_spans, keep=(ctx, x, wg, bias, experts, table, ws))
 
 
 def capture(torch, fn, reps=1):
@@ -281,7 +293,7 @@ def main():
         },
         "roofline": {"kernel": "gemm_bf16_kernel<SwiGLU> (first FFN GEMM with the activation)", "bound": "mfma",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": GEMM1_TRAFFIC_BYTES.get(cfg.name),
                      "launch_ms": float(gemm_ms[1]), "flops_per_launch": flops_gemm1},
     }
     if not args.no_cpu_baseline:
