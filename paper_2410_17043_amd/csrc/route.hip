@@ -176,6 +176,143 @@ __global__ __launch_bounds__(256) void route_kernel(const void* __restrict__ x, 
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Many experts (16 < E <= 64): one LANE per token.  The gate weight is first converted to fp64
+// and transposed to [H][64] (zero padded), so that the 64 weights of one hidden index are 512
+// contiguous bytes that every lane of a wave needs at the same time: they are fetched with scalar
+// loads and feed the FMAs as scalar operands (one v_fma_f64 per token, expert and hidden index;
+// nothing is converted or shuffled in the inner loop).  A block of S waves owns 64 tokens, wave s
+// the s-th part of the hidden dimension; token rows are staged through LDS in 128-byte pieces so
+// that memory sees whole lines while each lane reads its own row.  Partial logits meet in LDS;
+// wave 0 then picks the top-k of every token with one lane per token.
+template <int DT>
+__global__ __launch_bounds__(256) void wg_to_f64_kernel(const void* __restrict__ wg, int E, int H, double* __restrict__ out) {
+    const int i = blockIdx.x * 256 + threadIdx.x;          // one output element [h][e]
+    if (i >= H * 64) return;
+    const int h = i >> 6, e = i & 63;
+    double v = 0.0;
+    if (e < E) {
+        if (DT == MOE_BF16) v = (double)__uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(wg)[(size_t)e * H + h] << 16);
+        else v = (double)reinterpret_cast<const float*>(wg)[(size_t)e * H + h];
+    }
+    out[i] = v;
+}
+
+constexpr int kTokPitch = 144;                             // bytes per staged token row piece (128 + 16: spreads banks)
+
+template <int DT, int ET>
+__global__ __launch_bounds__(512) void route_tok_kernel(const void* __restrict__ x, const double* __restrict__ wg64t,
+                                                         const float* __restrict__ bias, int T, int H, int E, int k,
+                                                         int renorm, int S, int32_t* __restrict__ topk_idx,
+                                                         float* __restrict__ topk_w) {
+    constexpr int V = Chunk<DT>::V;                        // elements per 16 bytes
+    constexpr int PIECE = 8 * V;                           // hidden indices per 128-byte piece
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    double* zsum = reinterpret_cast<double*>(smem);        // [ET][64]: logits, expert-major so lanes (tokens) are contiguous
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    unsigned char* stage = smem + (size_t)ET * 64 * sizeof(double) + (size_t)wave * 64 * kTokPitch;
+    const int tok0 = blockIdx.x * 64;
+    const int n_piece = H / PIECE;                         // H * elem is a multiple of 128 for this kernel
+    const int per = (n_piece + S - 1) / S;
+    const int p_lo = wave * per, p_hi = min(p_lo + per, n_piece);
+    const int row_bytes = H * (DT == MOE_BF16 ? 2 : 4);
+    const unsigned char* xb = reinterpret_cast<const unsigned char*>(x);
+
+    double acc[ET];
+#pragma unroll
+    for (int e = 0; e < ET; ++e) acc[e] = 0.0;
+    for (int p = p_lo; p < p_hi; ++p) {
+        // 64 rows x 128 bytes: 8 lanes per row, 8 rows per load, whole lines
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int r = q * 8 + (lane >> 3);
+            const int t = min(tok0 + r, T - 1);
+            const u32x4 v = *reinterpret_cast<const u32x4*>(xb + (size_t)t * row_bytes + (size_t)p * 128 + (lane & 7) * 16);
+            *reinterpret_cast<u32x4*>(stage + r * kTokPitch + (lane & 7) * 16) = v;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            double xv[V];
+            Chunk<DT>::load(stage + lane * kTokPitch, c, xv);        // this lane's token, 16 bytes
+            const double* wrow = wg64t + ((size_t)p * PIECE + c * V) * 64;
+#pragma unroll
+            for (int v = 0; v < V; ++v)
+#pragma unroll
+                for (int e = 0; e < ET; ++e) acc[e] = fma(xv[v], wrow[v * 64 + e], acc[e]);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();                   // the stage is rewritten by the next piece
+    }
+    // partial logits of the S waves, added in wave order
+    for (int s = 0; s < S; ++s) {
+        if (wave == s) {
+#pragma unroll
+            for (int e = 0; e < ET; ++e) zsum[e * 64 + lane] = (s == 0 ? 0.0 : zsum[e * 64 + lane]) + acc[e];
+        }
+        __syncthreads();
+    }
+    if (wave != 0) return;
+    const int t = tok0 + lane;
+    double z[ET];
+#pragma unroll
+    for (int e = 0; e < ET; ++e) z[e] = (e < E) ? zsum[e * 64 + lane] + (bias ? (double)bias[e] : 0.0) : 0.0;
+    double zmax = 0.0, mass = 0.0, sel_sum = 0.0;
+    unsigned long long taken = 0;                           // bit e: expert e already chosen by this token
+    double wsel[MOE_MAX_K];
+    int esel[MOE_MAX_K];
+#pragma unroll
+    for (int j = 0; j < MOE_MAX_K; ++j) {
+        if (j < k) {
+            double best = 0.0;
+            int best_e = -1;
+#pragma unroll
+            for (int e = 0; e < ET; ++e) {
+                const bool free_e = e < E && !((taken >> e) & 1ull);
+                if (free_e && (best_e < 0 || z[e] > best)) { best = z[e]; best_e = e; }
+            }
+            taken |= 1ull << best_e;
+            if (j == 0) {
+                zmax = best;
+#pragma unroll
+                for (int e = 0; e < ET; ++e)
+                    if (e < E) mass += exp(z[e] - zmax);
+            }
+            esel[j] = best_e;
+            wsel[j] = exp(best - zmax) / mass;
+            sel_sum += wsel[j];
+        }
+    }
+    if (t < T) {
+#pragma unroll
+        for (int j = 0; j < MOE_MAX_K; ++j) {
+            if (j < k) {
+                topk_idx[(size_t)t * k + j] = esel[j];
+                topk_w[(size_t)t * k + j] = (float)(renorm ? wsel[j] / sel_sum : wsel[j]);
+            }
+        }
+    }
+}
+
+template <int DT, int ET>
+int launch_route_tok(const moe_ctx* c, const void* x, const void* wg, const float* bias, int32_t* idx, float* w,
+                     hipStream_t st) {
+    const moe_shape& s = c->s;
+    hipLaunchKernelGGL((wg_to_f64_kernel<DT>), dim3((s.H * 64 + 255) / 256), dim3(256), 0, st, wg, s.E, s.H, c->wg64t);
+    MOE_LAUNCH_CHECK("wg_to_f64_kernel");
+    const int groups = (s.T + 63) / 64;
+    int S = 1;                                              // waves per block: fill about 2048 wave slots, at most 8
+    while (S < 8 && groups * S < 2048) S *= 2;
+    const size_t lds = (size_t)ET * 64 * sizeof(double) + (size_t)S * 64 * kTokPitch;
+    hipLaunchKernelGGL((route_tok_kernel<DT, ET>), dim3(groups), dim3(64 * S), lds, st, x, c->wg64t, bias, s.T, s.H, s.E,
+                       s.k, s.renorm, S, idx, w);
+    MOE_LAUNCH_CHECK("route_tok_kernel");
+    return MOE_OK;
+}
+
 template <int DT, int TT, int ET>
 int launch_route(const moe_ctx* c, const void* x, const void* wg, const float* bias, int32_t* idx, float* w,
                  hipStream_t st) {
@@ -194,7 +331,10 @@ int route_dispatch(const moe_ctx* c, const void* x, const void* wg, const float*
     const int E = c->s.E;
     if (E <= 8) return launch_route<DT, 4, 8>(c, x, wg, bias, idx, w, st);
     if (E <= 16) return launch_route<DT, 4, 16>(c, x, wg, bias, idx, w, st);
-    if (E <= 32) return launch_route<DT, 2, 32>(c, x, wg, bias, idx, w, st);
+    // one lane per token needs whole 128-byte pieces of every row
+    const bool tok_ok = c->wg64t != nullptr && ((size_t)c->s.H * elem_size(c->s.dtype)) % 128 == 0;
+    if (E <= 32) return tok_ok ? launch_route_tok<DT, 32>(c, x, wg, bias, idx, w, st) : launch_route<DT, 2, 32>(c, x, wg, bias, idx, w, st);
+    if (E <= 64 && tok_ok) return launch_route_tok<DT, 64>(c, x, wg, bias, idx, w, st);
     return launch_route<DT, 1, 64>(c, x, wg, bias, idx, w, st);   // E > 64: several passes of 64 experts
 }
 
