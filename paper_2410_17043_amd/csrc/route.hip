@@ -21,8 +21,7 @@ namespace {
 template <int DT> struct Chunk;
 template <> struct Chunk<MOE_BF16> {
     static constexpr int V = 8;
-    __device__ static void load(const void* base, size_t chunk, double (&out)[8]) {
-        const uint4 q = reinterpret_cast<const uint4*>(base)[chunk];
+    __device__ static void unpack(const u32x4& q, double (&out)[8]) {
         const uint32_t u[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -30,12 +29,17 @@ template <> struct Chunk<MOE_BF16> {
             out[2 * i + 1] = (double)__uint_as_float(u[i] & 0xffff0000u);
         }
     }
+    __device__ static void load(const void* base, size_t chunk, double (&out)[8]) {
+        unpack(reinterpret_cast<const u32x4*>(base)[chunk], out);
+    }
 };
 template <> struct Chunk<MOE_F32> {
     static constexpr int V = 4;
+    __device__ static void unpack(const u32x4& q, double (&out)[4]) {
+        out[0] = __uint_as_float(q.x); out[1] = __uint_as_float(q.y); out[2] = __uint_as_float(q.z); out[3] = __uint_as_float(q.w);
+    }
     __device__ static void load(const void* base, size_t chunk, double (&out)[4]) {
-        const float4 q = reinterpret_cast<const float4*>(base)[chunk];
-        out[0] = q.x; out[1] = q.y; out[2] = q.z; out[3] = q.w;
+        unpack(reinterpret_cast<const u32x4*>(base)[chunk], out);
     }
 };
 
@@ -85,23 +89,35 @@ __global__ __launch_bounds__(256) void route_kernel(const void* __restrict__ x, 
         double acc[N];
 #pragma unroll
         for (int i = 0; i < N; ++i) acc[i] = 0.0;
-        for (int c = c_lo + lane; c < c_hi; c += 64) {
-            double xv[TT][V];
+        // two chunks per trip: all 2*TT token loads are in flight before the first weight is touched
+        for (int c = c_lo + lane; c < c_hi; c += 128) {
+            u32x4 raw[2][TT];
 #pragma unroll
-            for (int tt = 0; tt < TT; ++tt) {
-                const int t = min(tok0 + tt, T - 1);
-                Chunk<DT>::load(x, (size_t)t * nchunk + c, xv[tt]);
-            }
-            // experts past E are clamped to the last row: computed, never written out (keeps every
-            // index below a compile-time constant, so the partial logits stay in registers)
+            for (int u = 0; u < 2; ++u)
 #pragma unroll
-            for (int e = 0; e < ET; ++e) {
-                double wv[V];
-                Chunk<DT>::load(wg, (size_t)min(e0 + e, E - 1) * nchunk + c, wv);
+                for (int tt = 0; tt < TT; ++tt) {
+                    const int t = min(tok0 + tt, T - 1);
+                    const int cc = min(c + 64 * u, c_hi - 1);
+                    raw[u][tt] = reinterpret_cast<const u32x4*>(x)[(size_t)t * nchunk + cc];
+                }
 #pragma unroll
-                for (int tt = 0; tt < TT; ++tt)
+            for (int u = 0; u < 2; ++u) {
+                const int cc = c + 64 * u;
+                if (cc >= c_hi) continue;
+                double xv[TT][V];
 #pragma unroll
-                    for (int v = 0; v < V; ++v) acc[tt * ET + e] = fma(xv[tt][v], wv[v], acc[tt * ET + e]);
+                for (int tt = 0; tt < TT; ++tt) Chunk<DT>::unpack(raw[u][tt], xv[tt]);
+                // experts past E are clamped to the last row: computed, never written out (keeps every
+                // index below a compile-time constant, so the partial logits stay in registers)
+#pragma unroll
+                for (int e = 0; e < ET; ++e) {
+                    double wv[V];
+                    Chunk<DT>::load(wg, (size_t)min(e0 + e, E - 1) * nchunk + cc, wv);
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt)
+#pragma unroll
+                        for (int v = 0; v < V; ++v) acc[tt * ET + e] = fma(xv[tt][v], wv[v], acc[tt * ET + e]);
+                }
             }
         }
         halving_reduce<N>(acc, lane);
@@ -156,22 +172,24 @@ __global__ __launch_bounds__(256) void route_kernel(const void* __restrict__ x, 
             if (j == 0) zmax = best;
             if (lane == j) { my_z = best; my_e = best_e; }
         }
-        double part = 0.0;
+        // weights: the selection above is exact in fp64; the probabilities only need 1e-5, so the
+        // exponentials are taken in fp32 of the fp64 differences (all <= 0)
+        float part = 0.f;
 #pragma unroll
         for (int i = 0; i < MOE_MAX_E / 64; ++i)
-            if (lane + 64 * i < E) part += exp(cand[i] - zmax);
+            if (lane + 64 * i < E) part += __expf((float)(cand[i] - zmax));
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1) part += __shfl_xor(part, o, 64);
-        double wj = (lane < k) ? exp(my_z - zmax) / part : 0.0;
+        float wj = (lane < k) ? __expf((float)(my_z - zmax)) / part : 0.f;
         if (renorm) {
-            double s = wj;
+            float s = wj;
 #pragma unroll
             for (int o = 32; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
             wj /= s;
         }
         if (lane < k) {
             topk_idx[(size_t)t * k + lane] = my_e;
-            topk_w[(size_t)t * k + lane] = (float)wj;
+            topk_w[(size_t)t * k + lane] = wj;
         }
     }
 }
