@@ -147,8 +147,9 @@ size_t moe_ffn_workspace_bytes(int32_t R_max, int32_t H, int32_t F, int32_t act,
  *   experts     HOST [n_local], n_local <= 64
  *   out         device [R,H] dtype; rows outside every segment are left untouched
  *   workspace   device, >= moe_ffn_workspace_bytes(R,H,F,act,dtype), 256-byte aligned
- * bf16: H and F must be multiples of 128; the [R,F] intermediate is rounded to
- * bf16 once.  fp32: any sizes with H, F multiples of 4. */
+ * bf16: H and F must be multiples of 128 and H*F*2 bytes (one weight matrix) at
+ * most 4 GiB, else MOE_ESHAPE; the [R,F] intermediate is rounded to bf16 once.
+ * fp32: any sizes with H, F multiples of 4. */
 int moe_expert_ffn(const void* recv, int32_t R, const int32_t* seg_offset, const int32_t* seg_expert,
                    int32_t nseg, const moe_expert_w* experts, int32_t n_local, int32_t H, int32_t F,
                    int32_t act, int32_t dtype, void* out, void* workspace, size_t workspace_bytes,

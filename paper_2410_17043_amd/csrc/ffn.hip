@@ -254,7 +254,10 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
     int tile_m, tile_n;
     tile_of_block(blockIdx.x, gridDim.x, max_tiles_m, tiles_n, &tile_m, &tile_n);
     if (tile_m >= n_tiles_m) return;
-    const int row0 = m.row0[tile_m], nrows = m.nrows[tile_m], ex = m.expert[tile_m];
+    // everything read from the tile map is the same for the whole block: keep it in scalar registers
+    const int row0 = __builtin_amdgcn_readfirstlane(m.row0[tile_m]);
+    const int nrows = __builtin_amdgcn_readfirstlane(m.nrows[tile_m]);
+    const int ex = __builtin_amdgcn_readfirstlane(m.expert[tile_m]);
     auto pick = [&](int which) -> const uint16_t* {
         return reinterpret_cast<const uint16_t*>(which == 0 ? tab.w1[ex] : which == 1 ? tab.w_up[ex] : tab.w_down[ex]);
     };
@@ -262,30 +265,36 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
     const uint16_t* B1 = (EPI == EPI_SWIGLU) ? pick(which1) : B0;
     const int n0 = tile_n * NOUT;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform by construction; tell the compiler
     const int wm = wave >> 1, wn = wave & 1;
 
     // Direct-to-LDS staging.  A stage is 32 blocks of 1 KB (16 of A, 16 of B); wave w
-    // fills blocks w, w+4, ...: 4 of A and 4 of B per stage.
+    // fills blocks w, w+4, ...: 4 of A and 4 of B per stage.  Addresses are kept as a wave-uniform
+    // 64-bit base (advanced with k by scalar adds) plus a fixed 32-bit byte offset per lane, so a
+    // load costs no vector address arithmetic.
     int lr, lc;
     rc_of_slot(lane, &lr, &lc);
-    const uint16_t* a_src[4];
-    const uint16_t* b_src[4];
+    const char* a_base = reinterpret_cast<const char*>(A + (size_t)row0 * lda);
+    const char* b_base[4];
+    uint32_t a_voff[4], b_voff[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int r = (wave + 4 * i) * 16 + lr;              // tile row this lane fetches
-        a_src[i] = A + (size_t)(row0 + min(r, nrows - 1)) * lda + lc * 8;
+        const int blk = wave + 4 * i;                        // 16-row block of the tile (wave-uniform)
+        const int r = blk * 16 + lr;                         // tile row this lane fetches
+        a_voff[i] = (uint32_t)min(r, nrows - 1) * (uint32_t)lda * 2u + (uint32_t)lc * 16u;
         int col;
-        const uint16_t* Bm;
         if (EPI == EPI_SWIGLU) {
             const int w = r >> 7, sub = r & 127;
-            Bm = (sub < 64) ? B0 : B1;
+            b_base[i] = reinterpret_cast<const char*>(((blk * 16) & 64) ? B1 : B0);   // sub >= 64 for the whole block or not at all
             col = n0 + w * 64 + (sub & 63);
         } else {
-            Bm = B0;
+            b_base[i] = reinterpret_cast<const char*>(B0);
             col = n0 + r;
         }
-        b_src[i] = Bm + (size_t)min(col, N - 1) * K + lc * 8;
+        b_voff[i] = (uint32_t)min(col, N - 1) * (uint32_t)K * 2u + (uint32_t)lc * 16u;
+        // opaque to the optimiser from here on: it must stay a 32-bit lane offset next to a scalar base
+        asm volatile("" : "+v"(a_voff[i]), "+v"(b_voff[i]));
     }
     const int nk = K / BK;                                   // even: K is a multiple of 64
     // k-tiles t and t+1 (t even) into the stages t % 5 and (t+1) % 5; past the end the last pair is
@@ -294,15 +303,23 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
         t = min(t, nk - 2);
         unsigned char* s0 = lds + (t % STAGES) * kStageBytes;
         unsigned char* s1 = lds + ((t + 1) % STAGES) * kStageBytes;
-        const int k0 = t * BK;
+        const size_t kb = (size_t)t * BK * 2;                // byte offset of k-tile t inside a row
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             if (i < i_lo || i >= i_hi) continue;
             const int blk = (wave + 4 * i) * 1024;
-            __builtin_amdgcn_global_load_lds(a_src[i] + k0, (__attribute__((address_space(3))) void*)(s0 + blk), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds(a_src[i] + k0 + BK, (__attribute__((address_space(3))) void*)(s1 + blk), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds(b_src[i] + k0, (__attribute__((address_space(3))) void*)(s0 + kTileBytes + blk), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds(b_src[i] + k0 + BK, (__attribute__((address_space(3))) void*)(s1 + kTileBytes + blk), 16, 0, 0);
+            const char* ak = a_base + kb;
+            const char* bk = b_base[i] + kb;
+            uint32_t av = a_voff[i], bv = b_voff[i];
+            // opaque here, so that scalar base + zero-extended 32-bit lane offset is still visible when the
+            // load is selected (saddr form: half the address registers, no 64-bit vector add per load)
+            const char* ak1 = ak + BK * 2;
+            const char* bk1 = bk + BK * 2;
+            asm volatile("" : "+s"(ak), "+s"(bk), "+s"(ak1), "+s"(bk1), "+v"(av), "+v"(bv));
+            __builtin_amdgcn_global_load_lds(ak + av, (__attribute__((address_space(3))) void*)(s0 + blk), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(ak1 + av, (__attribute__((address_space(3))) void*)(s1 + blk), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(bk + bv, (__attribute__((address_space(3))) void*)(s0 + kTileBytes + blk), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(bk1 + bv, (__attribute__((address_space(3))) void*)(s1 + kTileBytes + blk), 16, 0, 0);
         }
     };
     auto issue_pair = [&](int t) { issue_part(t, 0, 4); };
@@ -385,7 +402,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
         mma(a0, b0);
         MOE_PHASE_SCHED()
         __builtin_amdgcn_sched_barrier(0);
-        __builtin_amdgcn_s_waitcnt(0x0F78);        // vmcnt(8)
+        __builtin_amdgcn_s_waitcnt(0x0F78);        // vmcnt(8): only groups 0 and 1 of the next pair may be outstanding
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
         load_frags(a0, b0, lds + ((kt + 2) % STAGES) * kStageBytes, 0);
@@ -490,6 +507,8 @@ static int ffn_impl(const void* recv, int32_t R, const int32_t* seg_offset, cons
         return moe_set_error(MOE_ESHAPE, "moe_expert_ffn: need 1 <= n_local <= %d and nseg <= %d", MOE_MAX_LOCAL, kMaxSeg);
     if (dtype == MOE_BF16 && (H % 128 != 0 || F % 128 != 0))
         return moe_set_error(MOE_ESHAPE, "moe_expert_ffn: bf16 needs H and F to be multiples of 128");
+    if (dtype == MOE_BF16 && (size_t)H * (size_t)F * 2 > 0xFFFFFFFFull)
+        return moe_set_error(MOE_ESHAPE, "moe_expert_ffn: bf16 weight matrices are limited to 4 GiB each (32-bit lane offsets)");
     if (dtype == MOE_F32 && (H % 4 != 0 || F % 4 != 0))
         return moe_set_error(MOE_EALIGN, "moe_expert_ffn: fp32 needs H and F to be multiples of 4");
     if (!aligned16(recv) || !aligned16(out) || (reinterpret_cast<uintptr_t>(workspace) & 255u))
