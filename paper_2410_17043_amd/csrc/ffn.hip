@@ -297,12 +297,12 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
         asm volatile("" : "+v"(a_voff[i]), "+v"(b_voff[i]));
     }
     const int nk = K / BK;                                   // even: K is a multiple of 64
-    // k-tiles t and t+1 (t even) into the stages t % 5 and (t+1) % 5; past the end the last pair is
-    // fetched again (into stages nobody reads) so that the count of outstanding loads stays uniform
-    auto issue_part = [&](int t, int i_lo, int i_hi) {
+    // k-tiles t and t+1 (t even) into the stages at LDS byte offsets so0 and so1; past the end the last pair is fetched again (into stages nobody reads any more) so that
+    // the count of outstanding loads stays uniform
+    auto issue_part = [&](int t, int so0, int so1, int i_lo, int i_hi) {
         t = min(t, nk - 2);
-        unsigned char* s0 = lds + (t % STAGES) * kStageBytes;
-        unsigned char* s1 = lds + ((t + 1) % STAGES) * kStageBytes;
+        unsigned char* s0 = lds + so0;
+        unsigned char* s1 = lds + so1;
         const size_t kb = (size_t)t * BK * 2;                // byte offset of k-tile t inside a row
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -310,7 +310,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
             const int blk = (wave + 4 * i) * 1024;
             const char* ak = a_base + kb;
             const char* bk = b_base[i] + kb;
-            uint32_t av = a_voff[i], bv = b_voff[i];
+            uint32_t &av = a_voff[i], &bv = b_voff[i];
             // opaque here, so that scalar base + zero-extended 32-bit lane offset is still visible when the
             // load is selected (saddr form: half the address registers, no 64-bit vector add per load)
             const char* ak1 = ak + BK * 2;
@@ -322,7 +322,6 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
             __builtin_amdgcn_global_load_lds(bk1 + bv, (__attribute__((address_space(3))) void*)(s1 + kTileBytes + blk), 16, 0, 0);
         }
     };
-    auto issue_pair = [&](int t) { issue_part(t, 0, 4); };
 
     f32x16 acc[4][4];                                        // [m-tile i][n-tile j], holds D^T: rows n, columns m
 #pragma unroll
@@ -332,24 +331,24 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    issue_pair(0);
-    issue_pair(2);
+    issue_part(0, 0, kStageBytes, 0, 4);
+    issue_part(2, 2 * kStageBytes, 3 * kStageBytes, 0, 3);   // its last group goes out in the first trip below
 
     const int fr = lane & 31, fk = lane >> 5;      // fragment row within a 32-row tile, which k-half
-    int a_off[4][2], b_off[4][2];                  // byte offsets inside a stage, per 32-row tile and k-step
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            a_off[i][s] = tile_off(wm * 128 + i * 32 + fr, 2 * s + fk);
-            b_off[i][s] = kTileBytes + tile_off(wn * 128 + i * 32 + fr, 2 * s + fk);
-        }
+    int a_off[2], b_off[2];                        // byte offsets inside a stage of 32-row tile 0, per k-step;
+#pragma unroll                                     // tile i lies 2 KB further (two 16-row blocks)
+    for (int s = 0; s < 2; ++s) {
+        a_off[s] = tile_off(wm * 128 + fr, 2 * s + fk);
+        b_off[s] = kTileBytes + tile_off(wn * 128 + fr, 2 * s + fk);
+    }
 
     auto load_frags = [&](bf16x8 (&af)[4], bf16x8 (&bfr)[4], const unsigned char* st, int s) {
+        const unsigned char* pa = st + a_off[s];
+        const unsigned char* pb = st + b_off[s];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const bf16x8*>(st + a_off[i][s]);
+        for (int i = 0; i < 4; ++i) af[i] = *reinterpret_cast<const bf16x8*>(pa + i * 2048);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(st + b_off[j][s]);
+        for (int j = 0; j < 4; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(pb + j * 2048);
     };
     auto mma = [&](const bf16x8 (&af)[4], const bf16x8 (&bfr)[4]) {
 #pragma unroll
@@ -371,7 +370,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
     // when the lines come from HBM, and a load that cannot be accepted stalls the wave's MFMA issue too.
     // A bare s_barrier is used: __syncthreads() would add a fence that waits for ALL outstanding loads.
     bf16x8 a0[4], b0[4], a1[4], b1[4];
-    __builtin_amdgcn_s_waitcnt(0x4F70);            // vmcnt(16): pair (0, 1) is in LDS
+    __builtin_amdgcn_s_waitcnt(0x0F7C);            // vmcnt(12): pair (0, 1) is in LDS
     __builtin_amdgcn_s_barrier();
     load_frags(a0, b0, lds, 0);
 #define MOE_PHASE_SCHED()                                                                      \
@@ -383,33 +382,40 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
         __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                                     \
         __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                                     \
     }
+    // so[j] is the LDS byte offset of the stage that holds k-tile kt + j; the five values rotate by two per
+    // trip, which keeps modulo arithmetic out of the instruction stream
+    int so[STAGES];
+#pragma unroll
+    for (int j = 0; j < STAGES; ++j) so[j] = j * kStageBytes;
     for (int kt = 0; kt < nk; kt += 2) {
         __builtin_amdgcn_sched_barrier(0);
-        load_frags(a1, b1, lds + (kt % STAGES) * kStageBytes, 1);
-        if (kt > 0) issue_part(kt + 2, 3, 4);
+        load_frags(a1, b1, lds + so[0], 1);
+        issue_part(kt + 2, so[2], so[3], 3, 4);
         mma(a0, b0);
         MOE_PHASE_SCHED()
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        load_frags(a0, b0, lds + ((kt + 1) % STAGES) * kStageBytes, 0);
-        issue_part(kt + 4, 0, 1);
+        load_frags(a0, b0, lds + so[1], 0);
+        issue_part(kt + 4, so[4], so[0], 0, 1);
         mma(a1, b1);
         MOE_PHASE_SCHED()
         __builtin_amdgcn_sched_barrier(0);
-        load_frags(a1, b1, lds + ((kt + 1) % STAGES) * kStageBytes, 1);
-        issue_part(kt + 4, 1, 2);
+        load_frags(a1, b1, lds + so[1], 1);
+        issue_part(kt + 4, so[4], so[0], 1, 2);
         mma(a0, b0);
         MOE_PHASE_SCHED()
         __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_waitcnt(0x0F78);        // vmcnt(8): only groups 0 and 1 of the next pair may be outstanding
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
-        load_frags(a0, b0, lds + ((kt + 2) % STAGES) * kStageBytes, 0);
-        issue_part(kt + 4, 2, 3);
+        load_frags(a0, b0, lds + so[2], 0);
+        issue_part(kt + 4, so[4], so[0], 2, 3);
         mma(a1, b1);
         MOE_PHASE_SCHED()
         __builtin_amdgcn_sched_barrier(0);
+        const int t0 = so[0], t1 = so[1];
+        so[0] = so[2]; so[1] = so[3]; so[2] = so[4]; so[3] = t0; so[4] = t1;
     }
 #undef MOE_PHASE_SCHED
     // no load may still target LDS, and no wave may still read operands, when LDS is reused below
