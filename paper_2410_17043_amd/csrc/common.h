@@ -36,7 +36,6 @@ struct moe_ctx {
     int32_t* raw_count;   // device [E]: slots per expert before the capacity rule
     int32_t* slot_rank;   // device [n_slots]: rank of a slot among the slots of its expert (-1: index out of range)
     const void* rank_src; // host: the topk_idx pointer slot_rank was computed from, NULL if stale
-    double* wg64t;        // device [H][64] fp64 copy of the gate weight, transposed and zero padded (only for 16 < E <= 64)
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // 16-byte load/store unit

@@ -60,16 +60,6 @@ extern "C" int moe_ctx_create(moe_ctx** out, const moe_shape* shape) {
     }
     c->raw_count = c->block_hist + (size_t)c->n_blocks * shape->E;
     c->slot_rank = c->raw_count + shape->E;
-    c->wg64t = nullptr;
-    if (shape->E > 16 && shape->E <= 64) {
-        const size_t wbytes = (size_t)shape->H * 64 * sizeof(double);
-        e = hipMalloc((void**)&c->wg64t, wbytes);
-        if (e != hipSuccess) {
-            (void)hipFree(c->block_hist);
-            delete c;
-            return moe_set_error(e == hipErrorOutOfMemory ? MOE_ENOMEM : MOE_EHIP, "hipMalloc(%zu): %s", wbytes, hipGetErrorString(e));
-        }
-    }
     *out = c;
     return MOE_OK;
 }
@@ -83,10 +73,6 @@ extern "C" int moe_ctx_invalidate(moe_ctx* ctx) {
 extern "C" int moe_ctx_destroy(moe_ctx* ctx) {
     if (!ctx) return MOE_OK;
     hipError_t e = hipFree(ctx->block_hist);
-    if (ctx->wg64t) {
-        hipError_t e2 = hipFree(ctx->wg64t);
-        if (e == hipSuccess) e = e2;
-    }
     delete ctx;
     if (e != hipSuccess) return moe_set_error(MOE_EHIP, "hipFree: %s", hipGetErrorString(e));
     return MOE_OK;

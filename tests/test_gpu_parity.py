@@ -42,6 +42,9 @@ ROUTE_CASES = [
     small("c5_finegrained", T=65, H=264, E=160, k=9, G=16),
     small("c1_tiny_fp32", T=50, H=36, E=200, k=16, G=8),
     small("c2_mixtral", T=33, H=64, E=24, k=4, G=8),
+    small("c2_mixtral", T=17, H=8, E=17, k=2, G=1),              # one 16-byte chunk per row, one expert past a tile
+    small("c5_finegrained", T=100, H=520, E=65, k=6, G=5),       # second pass of 64 experts holds a single expert
+    small("c3_switch", T=40, H=1024, E=256, k=16, G=64),         # the limits of E, k and G
 ]
 
 
