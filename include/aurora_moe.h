@@ -134,7 +134,8 @@ typedef struct {
 } moe_expert_w;
 
 /* Bytes of device workspace moe_expert_ffn needs for up to R_max rows (the
- * [R,F] intermediate plus a tile map); 0 if an argument is invalid. */
+ * [R,F] intermediate, a tile map and, for bf16, 64 MiB of fp32 partial tiles);
+ * 0 if an argument is invalid. */
 size_t moe_ffn_workspace_bytes(int32_t R_max, int32_t H, int32_t F, int32_t act, int32_t dtype);
 
 /* Expert FFN (Sec. 2.1) over the rows this GPU received: rows

@@ -108,13 +108,14 @@ template <int EPI> __device__ __forceinline__ float epilogue(float a, float b) {
     return a;
 }
 
-// Remap the linear block id so that (1) the blocks resident on one XCD (ids equal
-// mod 8) get consecutive virtual ids and (2) consecutive virtual ids walk GROUP_M
-// M-tiles before moving to the next N-tile, so an XCD's L2 holds few distinct tiles.
-__device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m, int tiles_n, int* tm, int* tn) {
+// Remap tile number `id` of `total` = tiles_m * tiles_n so that (1) the blocks resident on one XCD
+// (ids equal mod 8) get consecutive virtual ids and (2) consecutive virtual ids walk GROUP_M
+// M-tiles before moving to the next N-tile, so an XCD's L2 holds few distinct tiles.  A
+// bijection on [0, total) for every total.
+__device__ __forceinline__ void tile_of_block(int id, int total, int tiles_m, int tiles_n, int* tm, int* tn) {
     constexpr int GROUP_M = 8;
-    int vid = bid;
-    if (nblocks % 8 == 0) vid = (bid % 8) * (nblocks / 8) + bid / 8;
+    const int x = id % 8;                                    // XCD x owns ids x, x + 8, ...
+    const int vid = x * (total / 8) + min(x, total % 8) + id / 8;
     const int per_group = GROUP_M * tiles_n;
     const int g = vid / per_group;
     const int first_m = g * GROUP_M;
@@ -123,6 +124,35 @@ __device__ __forceinline__ void tile_of_block(int bid, int nblocks, int tiles_m,
     *tm = first_m + in_g % gsz;
     *tn = in_g / gsz;
 }
+
+// Tail splitting.  The grid runs in rounds of `ncu` tiles (one block per CU); the tiles of a last,
+// mostly empty round would leave most CUs idle for a whole tile time.  When that round has at most
+// ncu / 4 tiles, each of them is cut along K into `parts` pieces that run as separate blocks
+// (1/parts of a tile time) and write fp32 partial tiles; a second small kernel adds the pieces
+// of a tile in piece order and applies the epilogue.  Everything here depends
+// only on the shapes, so results do not vary from run to run.
+struct TailPlan {
+    int n_full;        // tiles handled whole: ids [0, n_full)
+    int n_tail;        // tiles cut in pieces: ids [n_full, n_full + n_tail)
+    int parts;         // pieces per tail tile (1: no tail)
+    int pairs_per;     // k-tile pairs per piece
+};
+__device__ __forceinline__ TailPlan plan_tail(int total, int ncu, int nk) {
+    TailPlan p;
+    p.n_full = total; p.n_tail = 0; p.parts = 1; p.pairs_per = nk / 2;
+    const int rem = total % ncu;
+    const int npairs = nk / 2;
+    if (rem == 0) return p;
+    // 4 to 8 pieces of at least 16 k-tiles: fewer do not pay for the extra pass, more only add partial tiles
+    const int parts = min(min(ncu / rem, npairs / 8), 8);
+    if (parts < 4) return p;
+    p.pairs_per = (npairs + parts - 1) / parts;
+    p.parts = (npairs + p.pairs_per - 1) / p.pairs_per;
+    p.n_tail = rem;
+    p.n_full = total - rem;
+    return p;
+}
+constexpr size_t kPartialBytes = (size_t)256 * 256 * sizeof(float);   // one fp32 partial tile
 
 // ------------------------------------------------------------------------------------ fp32
 // C[r, n] = epi( sum_k A[r,k] * B0[n,k], sum_k A[r,k] * B1[n,k] ), 64x64 tile, 4x4 per thread.
@@ -188,6 +218,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int BM = 256, BN = 256, BK = 32, STAGES = 5;
@@ -228,6 +259,64 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     return *reinterpret_cast<const uint32_t*>(&b);
 }
 
+// Epilogue of a tile in two steps: activation on registers, pack to bf16 and write to LDS (which
+// must be idle) for one 32-row tile i of every wave; then whole-line stores of row tiles
+// [i_lo, i_hi).  acc_i[j][e] is output row  i*32 + lane%32  and output column
+// j*32 + (e/4)*8 + (lane/32)*4 + e%4  of the wave's 128 x (NJ*32) block.
+template <int EPI> struct EpiGeom {
+    static constexpr int NOUT = (EPI == EPI_SWIGLU) ? 128 : 256;   // output columns per block
+    static constexpr int NW = NOUT / 2;                            // output columns per wave
+    static constexpr int NJ = NW / 32;                             // 32-wide output column tiles per wave
+    static constexpr int PITCH = NW * 2 + 8;                       // bytes; the +8 spreads the 32 rows of a write over all banks
+};
+template <int EPI>
+__device__ __forceinline__ void stage_rows(const f32x16 (&acc_i)[4], int i, unsigned char* lds) {
+    using G = EpiGeom<EPI>;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int fr = lane & 31, fk = lane >> 5;
+    unsigned char* region = lds + wave * (128 * G::PITCH);
+#pragma unroll
+    for (int j = 0; j < G::NJ; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            float v[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float up = (EPI == EPI_SWIGLU) ? acc_i[j + 2][4 * g + t] : 0.f;
+                v[t] = epilogue_bf16<EPI>(acc_i[j][4 * g + t], up);
+            }
+            const u32x2 p = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+            *reinterpret_cast<u32x2*>(region + (i * 32 + fr) * G::PITCH + (j * 32 + g * 8 + fk * 4) * 2) = p;
+        }
+}
+template <int EPI>
+__device__ __forceinline__ void flush_rows(int i_lo, int i_hi, const unsigned char* lds, int row0, int nrows, int n0, int N,
+                                           uint16_t* __restrict__ C, int ldc) {
+    using G = EpiGeom<EPI>;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const unsigned char* region = lds + wave * (128 * G::PITCH);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");     // a wave reads back only what it wrote itself
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    constexpr int LPR = G::NW * 2 / 16;            // lanes per output row (16 bytes each)
+    constexpr int RPI = 64 / LPR;                  // rows per store instruction
+    const int sub_r = lane / LPR, sub_c = lane % LPR;
+    const int col = n0 + wn * G::NW + sub_c * 8;
+#pragma unroll 4
+    for (int it = i_lo * 32 / RPI; it < i_hi * 32 / RPI; ++it) {
+        const int r = it * RPI + sub_r;            // row inside this wave's 128
+        const unsigned char* src = region + r * G::PITCH + sub_c * 16;
+        const u32x2 lo = *reinterpret_cast<const u32x2*>(src);
+        const u32x2 hi = *reinterpret_cast<const u32x2*>(src + 8);
+        const int gr = wm * 128 + r;
+        if (gr < nrows && col < N) {
+            const u32x4 q = {lo.x, lo.y, hi.x, hi.y};
+            *reinterpret_cast<u32x4*>(C + (size_t)(row0 + gr) * ldc + col) = q;
+        }
+    }
+}
+
 // C[r, n] = epi(sum_k A[r,k] B0[n,k] , sum_k A[r,k] B1[n,k]) for one 256-row M-tile and one
 // N-tile.  SwiGLU: the B tile's 256 rows are, per wave-column wn (64 output columns), 64 rows
 // of W1 followed by the 64 rows of Wu for the same columns, so the gate and the up product of
@@ -244,16 +333,22 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 template <int EPI>
 __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __restrict__ A, int lda, TileMap m,
                                                            ExpertTable tab, int which0, int which1, int N, int K,
-                                                           uint16_t* __restrict__ C, int ldc, int tiles_n,
-                                                           int max_tiles_m) {
+                                                           uint16_t* __restrict__ C, int ldc, int tiles_n, int ncu,
+                                                           float* __restrict__ partial) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     constexpr int NOUT = (EPI == EPI_SWIGLU) ? 128 : 256;                  // output columns per block
-    constexpr int NW = NOUT / 2;                                           // output columns per wave
-    constexpr int NJ = NW / 32;                                            // 32-wide output column tiles per wave
     const int n_tiles_m = *m.n_tiles;
+    const int total = n_tiles_m * tiles_n;
+    const TailPlan plan = plan_tail(total, ncu, K / BK);
+    int tile_id = blockIdx.x, piece = -1;                                   // piece < 0: the whole K range
+    if ((int)blockIdx.x >= plan.n_full) {
+        const int j = blockIdx.x - plan.n_full;
+        if (j >= plan.n_tail * plan.parts) return;
+        tile_id = plan.n_full + j % plan.n_tail;
+        piece = j / plan.n_tail;
+    }
     int tile_m, tile_n;
-    tile_of_block(blockIdx.x, gridDim.x, max_tiles_m, tiles_n, &tile_m, &tile_n);
-    if (tile_m >= n_tiles_m) return;
+    tile_of_block(tile_id, total, n_tiles_m, tiles_n, &tile_m, &tile_n);
     // everything read from the tile map is the same for the whole block: keep it in scalar registers
     const int row0 = __builtin_amdgcn_readfirstlane(m.row0[tile_m]);
     const int nrows = __builtin_amdgcn_readfirstlane(m.nrows[tile_m]);
@@ -275,7 +370,10 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
     // load costs no vector address arithmetic.
     int lr, lc;
     rc_of_slot(lane, &lr, &lc);
-    const char* a_base = reinterpret_cast<const char*>(A + (size_t)row0 * lda);
+    // k-tiles [kt_lo, kt_lo + nk) of the row: everything for a whole tile, one piece for a tail tile
+    const int kt_lo = (piece < 0) ? 0 : piece * plan.pairs_per * 2;
+    const int nk = (piece < 0) ? K / BK : min(plan.pairs_per * 2, K / BK - kt_lo);   // even: K is a multiple of 64
+    const char* a_base = reinterpret_cast<const char*>(A + (size_t)row0 * lda) + (size_t)kt_lo * BK * 2;
     const char* b_base[4];
     uint32_t a_voff[4], b_voff[4];
 #pragma unroll
@@ -286,17 +384,16 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
         int col;
         if (EPI == EPI_SWIGLU) {
             const int w = r >> 7, sub = r & 127;
-            b_base[i] = reinterpret_cast<const char*>(((blk * 16) & 64) ? B1 : B0);   // sub >= 64 for the whole block or not at all
+            b_base[i] = reinterpret_cast<const char*>(((blk * 16) & 64) ? B1 : B0) + (size_t)kt_lo * BK * 2;   // sub >= 64 for the whole block or not at all
             col = n0 + w * 64 + (sub & 63);
         } else {
-            b_base[i] = reinterpret_cast<const char*>(B0);
+            b_base[i] = reinterpret_cast<const char*>(B0) + (size_t)kt_lo * BK * 2;
             col = n0 + r;
         }
         b_voff[i] = (uint32_t)min(col, N - 1) * (uint32_t)K * 2u + (uint32_t)lc * 16u;
         // opaque to the optimiser from here on: it must stay a 32-bit lane offset next to a scalar base
         asm volatile("" : "+v"(a_voff[i]), "+v"(b_voff[i]));
     }
-    const int nk = K / BK;                                   // even: K is a multiple of 64
     // k-tiles t and t+1 (t even) into the stages at LDS byte offsets so0 and so1; past the end the last pair is fetched again (into stages nobody reads any more) so that
     // the count of outstanding loads stays uniform
     auto issue_part = [&](int t, int so0, int so1, int i_lo, int i_hi) {
@@ -422,63 +519,100 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
     __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0) lgkmcnt(0)
     __builtin_amdgcn_s_barrier();
 
-    // Epilogue.  acc[i][j][e] is output row  i*32 + lane%32  and output column
-    // j*32 + (e/4)*8 + (lane/32)*4 + e%4  of this wave's 128 x (NJ*32) block.
-    constexpr int PITCH = NW * 2 + 8;              // bytes; the +8 spreads the 32 rows of a write over all banks
-    unsigned char* region = lds + wave * (128 * PITCH);
+    if (piece >= 0) {
+        // a piece of a tail tile: the raw accumulators, 16 bytes per lane and store (whole 4 KB per store)
+        f32x4* dst = reinterpret_cast<f32x4*>(reinterpret_cast<char*>(partial) +
+                                              ((size_t)(tile_id - plan.n_full) * plan.parts + piece) * kPartialBytes);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < NJ; ++j)
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                float v[4];
-#pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const float up = (EPI == EPI_SWIGLU) ? acc[i][j + 2][4 * g + t] : 0.f;
-                    v[t] = epilogue_bf16<EPI>(acc[i][j][4 * g + t], up);
+                for (int q = 0; q < 4; ++q) {
+                    const f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                    dst[((i * 4 + j) * 4 + q) * 256 + tid] = v;
                 }
-                const u32x2 p = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
-                *reinterpret_cast<u32x2*>(region + (i * 32 + fr) * PITCH + (j * 32 + g * 8 + fk * 4) * 2) = p;
-            }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    constexpr int LPR = NW * 2 / 16;               // lanes per output row (16 bytes each)
-    constexpr int RPI = 64 / LPR;                  // rows per store instruction
-    const int sub_r = lane / LPR, sub_c = lane % LPR;
-    const int col = n0 + wn * NW + sub_c * 8;
-#pragma unroll 4
-    for (int it = 0; it < 128 / RPI; ++it) {
-        const int r = it * RPI + sub_r;            // row inside this wave's 128
-        const unsigned char* src = region + r * PITCH + sub_c * 16;
-        const u32x2 lo = *reinterpret_cast<const u32x2*>(src);
-        const u32x2 hi = *reinterpret_cast<const u32x2*>(src + 8);
-        const int gr = wm * 128 + r;
-        if (gr < nrows && col < N) {
-            const u32x4 q = {lo.x, lo.y, hi.x, hi.y};
-            *reinterpret_cast<u32x4*>(C + (size_t)(row0 + gr) * ldc + col) = q;
-        }
+        return;
     }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) stage_rows<EPI>(acc[i], i, lds);
+    flush_rows<EPI>(0, 4, lds, row0, nrows, n0, N, C, ldc);
+}
+
+// Adds the pieces of one 32-row tile per wave (blockIdx.x % 4) of tail tile blockIdx.x / 4 in piece
+// order and finishes those rows like a whole tile's.
+template <int EPI>
+__global__ __launch_bounds__(256) void gemm_bf16_tail_kernel(TileMap m, int N, int K, uint16_t* __restrict__ C, int ldc,
+                                                             int tiles_n, int ncu, const float* __restrict__ partial) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    const int n_tiles_m = *m.n_tiles;
+    const int total = n_tiles_m * tiles_n;
+    const TailPlan plan = plan_tail(total, ncu, K / BK);
+    const int tt = blockIdx.x >> 2, i = blockIdx.x & 3;
+    if (tt >= plan.n_tail) return;
+    int tile_m, tile_n;
+    tile_of_block(plan.n_full + tt, total, n_tiles_m, tiles_n, &tile_m, &tile_n);
+    const int row0 = m.row0[tile_m], nrows = m.nrows[tile_m];
+    const int tid = threadIdx.x;
+    const f32x4* src = reinterpret_cast<const f32x4*>(reinterpret_cast<const char*>(partial) +
+                                                      (size_t)tt * plan.parts * kPartialBytes) + (size_t)i * 16 * 256 + tid;
+    f32x4 sum[16];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) sum[q] = src[q * 256];
+    for (int p = 1; p < plan.parts; ++p) {
+        const f32x4* sp = src + (size_t)p * (kPartialBytes / 16);
+#pragma unroll
+        for (int q = 0; q < 16; ++q) sum[q] += sp[q * 256];
+    }
+    f32x16 acc_i[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc_i[j][4 * q + t] = sum[j * 4 + q][t];
+    stage_rows<EPI>(acc_i, i, lds);
+    flush_rows<EPI>(i, i + 1, lds, row0, nrows, tile_n * EpiGeom<EPI>::NOUT, N, C, ldc);
+}
+
+constexpr int kMaxCU = 256;                    // tail pieces per launch, at most: sizes the partial-tile workspace
+
+// number of CUs of the current device (a round of the grid), at most kMaxCU
+int round_size() {
+    static int ncu = 0;
+    if (ncu == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = kMaxCU;
+        ncu = n < kMaxCU ? n : kMaxCU;
+    }
+    return ncu;
 }
 
 template <int EPI>
 int launch_bf16(const void* A, int lda, const TileMap& m, const ExpertTable& tab, int which0, int which1, int N, int K,
-                void* C, int ldc, int R, int nseg, hipStream_t st) {
+                void* C, int ldc, int R, int nseg, float* partial, hipStream_t st) {
     const int nout = (EPI == EPI_SWIGLU) ? 128 : 256;
     const int tiles_n = (N + nout - 1) / nout;
     const int max_tiles_m = (R + BM - 1) / BM + nseg;
+    const int ncu = round_size();
     const size_t lds = (size_t)kLdsBytes;
     static bool attr_done = false;
     if (!attr_done) {
         MOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<EPI>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        MOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_tail_kernel<EPI>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_done = true;
     }
-    hipLaunchKernelGGL((gemm_bf16_kernel<EPI>), dim3(max_tiles_m * tiles_n), dim3(256), lds, st,
+    // whole tiles first, then at most ncu pieces of tail tiles; blocks past the real tile count exit at once
+    hipLaunchKernelGGL((gemm_bf16_kernel<EPI>), dim3(max_tiles_m * tiles_n + ncu), dim3(256), lds, st,
                        reinterpret_cast<const uint16_t*>(A), lda, m, tab, which0, which1, N, K,
-                       reinterpret_cast<uint16_t*>(C), ldc, tiles_n, max_tiles_m);
+                       reinterpret_cast<uint16_t*>(C), ldc, tiles_n, ncu, partial);
     MOE_LAUNCH_CHECK("gemm_bf16_kernel");
+    hipLaunchKernelGGL((gemm_bf16_tail_kernel<EPI>), dim3(ncu), dim3(256), lds, st, m, N, K,   // ncu / 4 tiles at most, 4 blocks each
+                       reinterpret_cast<uint16_t*>(C), ldc, tiles_n, ncu, partial);
+    MOE_LAUNCH_CHECK("gemm_bf16_tail_kernel");
     return MOE_OK;
 }
 
@@ -498,7 +632,8 @@ int launch_f32(const void* A, int lda, const TileMap& m, const ExpertTable& tab,
 
 extern "C" size_t moe_ffn_workspace_bytes(int32_t R_max, int32_t H, int32_t F, int32_t act, int32_t dtype) {
     if (R_max < 0 || H <= 0 || F <= 0 || act < 0 || act > 2 || (dtype != MOE_F32 && dtype != MOE_BF16)) return 0;
-    return tilemap_bytes(R_max) + align256((size_t)R_max * F * elem_size(dtype)) + 256;
+    const size_t partial = (dtype == MOE_BF16) ? (size_t)kMaxCU * kPartialBytes : 0;   // pieces of tail tiles
+    return tilemap_bytes(R_max) + align256((size_t)R_max * F * elem_size(dtype)) + partial + 256;
 }
 
 static int ffn_impl(const void* recv, int32_t R, const int32_t* seg_offset, const int32_t* seg_expert, int32_t nseg,
@@ -538,6 +673,7 @@ static int ffn_impl(const void* recv, int32_t R, const int32_t* seg_offset, cons
     }
     TileMap m = tilemap_at(workspace, R);
     void* hmid = reinterpret_cast<char*>(workspace) + tilemap_bytes(R);
+    float* partial = reinterpret_cast<float*>(reinterpret_cast<char*>(hmid) + align256((size_t)R * F * elem_size(dtype)));
     const int bm = (dtype == MOE_BF16) ? BM : 64;
     if (ev) MOE_HIP(hipEventRecord(ev[0], st));
     hipLaunchKernelGGL(tilemap_kernel, dim3(1), dim3(256), 0, st, seg_offset, seg_expert, nseg, R, bm, n_local, m);
@@ -545,12 +681,12 @@ static int ffn_impl(const void* recv, int32_t R, const int32_t* seg_offset, cons
     if (ev) MOE_HIP(hipEventRecord(ev[1], st));
     int rc;
     if (dtype == MOE_BF16) {
-        if (act == MOE_ACT_SWIGLU) rc = launch_bf16<EPI_SWIGLU>(recv, H, m, tab, 0, 1, F, H, hmid, F, R, nseg, st);
-        else if (act == MOE_ACT_GELU_MLP) rc = launch_bf16<EPI_GELU>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, st);
-        else rc = launch_bf16<EPI_SILU>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, st);
+        if (act == MOE_ACT_SWIGLU) rc = launch_bf16<EPI_SWIGLU>(recv, H, m, tab, 0, 1, F, H, hmid, F, R, nseg, partial, st);
+        else if (act == MOE_ACT_GELU_MLP) rc = launch_bf16<EPI_GELU>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, partial, st);
+        else rc = launch_bf16<EPI_SILU>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, partial, st);
         if (rc != MOE_OK) return rc;
         if (ev) MOE_HIP(hipEventRecord(ev[2], st));
-        rc = launch_bf16<EPI_PLAIN>(hmid, F, m, tab, 2, 2, H, F, out, H, R, nseg, st);
+        rc = launch_bf16<EPI_PLAIN>(hmid, F, m, tab, 2, 2, H, F, out, H, R, nseg, partial, st);
     } else {
         if (act == MOE_ACT_SWIGLU) rc = launch_f32<EPI_SWIGLU>(recv, H, m, tab, 0, 1, F, H, hmid, F, R, nseg, st);
         else if (act == MOE_ACT_GELU_MLP) rc = launch_f32<EPI_GELU>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, st);

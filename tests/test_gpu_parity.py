@@ -196,6 +196,10 @@ FFN_CASES = [
     ("bf16", 1, 523, 256, 512, 3, 7),
     ("bf16", 0, 300, 128, 256, 2, 3),
     ("bf16", 2, 1029, 512, 1408, 4, 9),
+    # few tiles and a long K: the tiles of the last, mostly empty round are cut along K into pieces
+    ("bf16", 2, 300, 2048, 2048, 1, 1),
+    ("bf16", 1, 700, 2048, 2304, 3, 6),
+    ("bf16", 0, 257, 3072, 2048, 2, 2),
 ]
 
 
