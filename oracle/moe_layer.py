@@ -140,6 +140,57 @@ def dispatch(x, idx, expert_to_gpu, dest_order, capacity=0):
             "seg_expert": np.asarray(seg_expert, dtype=np.int32), "n_rows": len(row_to_slot)}
 
 
+def dispatch_chunks(x, idx, expert_to_gpu, chunks, capacity=0):
+    """Send buffer of one GPU laid out for a preemptive schedule (Appendix A: in every
+    time slot a GPU sends to one GPU, and a flow may be served in several slots).
+
+    The kept slots of a destination form one sequence: expert by expert (ascending
+    id), inside an expert by ascending slot id - the order `dispatch` uses.
+    ``chunks`` is a list of (dest, rows): chunk c carries the next ``rows`` slots of
+    its destination's sequence, fewer (possibly none) if the sequence runs out; a
+    chunk whose dest is no GPU is empty.  What the plan did not cover follows after
+    the last chunk, destination by destination in ascending GPU id.  The buffer is
+    the concatenation of the chunks.  A piece is a maximal run of rows of one chunk
+    and one expert; pieces are listed in buffer order.
+    Returns dict(send_buf, slot_to_row (-1 = dropped), row_to_slot, chunk_offset
+    [len(chunks)+G+1], piece_offset[P+1], piece_expert[P], n_rows).
+    """
+    x = np.asarray(x)
+    idx = np.asarray(idx)
+    T, k = idx.shape
+    G = int(max(expert_to_gpu)) + 1
+    _, _, _, keep = traffic(idx, expert_to_gpu, G, capacity)
+    flat = idx.reshape(-1)
+    seq = [[] for _ in range(G)]                            # per destination: its slots in order
+    for e in range(len(expert_to_gpu)):
+        seq[expert_to_gpu[e]].extend(int(s) for s in np.nonzero(keep & (flat == e))[0])
+    taken = [0] * G
+    row_to_slot, chunk_offset = [], [0]
+    for dest, rows in list(chunks) + [(d, None) for d in range(G)]:
+        if 0 <= dest < G:
+            hi = len(seq[dest]) if rows is None else min(len(seq[dest]), taken[dest] + max(int(rows), 0))
+            row_to_slot.extend(seq[dest][taken[dest]:hi])
+            taken[dest] = hi
+        chunk_offset.append(len(row_to_slot))
+    slot_to_row = np.full(T * k, -1, dtype=np.int32)
+    for r, s in enumerate(row_to_slot):
+        slot_to_row[s] = r
+    piece_start, piece_expert = [], []
+    for c in range(len(chunk_offset) - 1):
+        for r in range(chunk_offset[c], chunk_offset[c + 1]):
+            e = int(flat[row_to_slot[r]])
+            if r == chunk_offset[c] or e != piece_expert[-1]:
+                piece_start.append(r)
+                piece_expert.append(e)
+    piece_offset = piece_start + [len(row_to_slot)]
+    row_to_slot = np.asarray(row_to_slot, dtype=np.int32)
+    send_buf = x[row_to_slot // k] if len(row_to_slot) else np.zeros((0, x.shape[1]), x.dtype)
+    return {"send_buf": send_buf, "slot_to_row": slot_to_row, "row_to_slot": row_to_slot,
+            "chunk_offset": np.asarray(chunk_offset, dtype=np.int32),
+            "piece_offset": np.asarray(piece_offset, dtype=np.int32),
+            "piece_expert": np.asarray(piece_expert, dtype=np.int32), "n_rows": len(row_to_slot)}
+
+
 # ----------------------------------------------------------------- expert FFN (Sec. 2.1)
 def _silu(a):
     return a / (1.0 + np.exp(-a))

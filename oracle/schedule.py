@@ -127,6 +127,32 @@ def rounds(D, B=None):
     return out, bm
 
 
+def chunks_from_rounds(D, B, g):
+    """Chunk list [(dest, tokens)] of GPU g for the schedule of `rounds`: one chunk per
+    round in which g sends real traffic.  Tokens are whole: a chunk carries the
+    cumulative real traffic g has sent to that destination by the end of the round
+    (scaled amount times min(B_g, B_dest)), rounded down, minus what its earlier
+    chunks carried.  The cumulative amount ends at d_g,dest exactly, so nothing is
+    left over.  Returns (chunks, round_of_chunk)."""
+    sched, _ = rounds(D, B)
+    n = len(D)
+    rate = [Fraction(1) if B is None else min(Fraction(B[g]), Fraction(B[j])) for j in range(n)]
+    cum = [Fraction(0)] * n
+    sent = [0] * n
+    chunks, which = [], []
+    for r, (dst, _tau, real) in enumerate(sched):
+        j = dst[g]
+        if j < 0:
+            continue
+        cum[j] += real[g] * rate[j]
+        rows = int(cum[j]) - sent[j]                        # floor of an exact fraction
+        if rows > 0:
+            chunks.append((j, rows))
+            which.append(r)
+            sent[j] += rows
+    return chunks, which
+
+
 def simulate(D, B, order):
     """Completion time of an all-to-all when GPU i sends to the destinations in
     order[i] one after the other (big-switch model of Sec. 2.4).

@@ -135,6 +135,61 @@ def test_dispatch_invariants_all_24_orders(capacity):
             assert np.all(np.diff(seg) > 0)                                       # stable inside a segment
 
 
+def test_chunked_dispatch_reduces_to_dispatch_and_keeps_destination_sequences():
+    r = rng(70)
+    T, k, E, G, H = 96, 2, 12, 4, 3
+    x = r.standard_normal((T, H))
+    idx = np.stack([r.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
+    e2g = np.arange(E) % G                                  # experts of a GPU are not contiguous ids
+    flat = idx.reshape(-1)
+    for capacity in (0, 11):
+        ec, dc, nd, keep = O.traffic(idx, e2g, G, capacity)
+        # (1) one unbounded chunk per destination IS the non-preemptive layout of `dispatch`
+        for order in [(0, 1, 2, 3), (2, 0, 3, 1), (3, 2, 1, 0)]:
+            a = O.dispatch(x, idx, e2g, order, capacity)
+            b = O.dispatch_chunks(x, idx, e2g, [(g, 10 ** 9) for g in order], capacity)
+            assert np.array_equal(a["slot_to_row"], b["slot_to_row"])
+            assert np.array_equal(a["row_to_slot"], b["row_to_slot"])
+            assert np.array_equal(a["send_buf"], b["send_buf"])
+        # (2) an empty plan: everything is left over, destination by destination in GPU order
+        a = O.dispatch(x, idx, e2g, range(G), capacity)
+        b = O.dispatch_chunks(x, idx, e2g, [], capacity)
+        assert np.array_equal(a["row_to_slot"], b["row_to_slot"])
+        # (3) random preemptive plans, with too little, too much and unknown destinations
+        whole = {g: [s for e in range(E) if e2g[e] == g for s in np.nonzero(keep & (flat == e))[0]] for g in range(G)}
+        for trial in range(20):
+            chunks = [(int(r.integers(-1, G + 1)), int(r.integers(0, 30))) for _ in range(int(r.integers(0, 14)))]
+            d = O.dispatch_chunks(x, idx, e2g, chunks, capacity)
+            r2s, s2r, co = d["row_to_slot"], d["slot_to_row"], d["chunk_offset"]
+            assert d["n_rows"] == T * k - nd == len(r2s)
+            assert sorted(r2s.tolist()) == sorted(np.nonzero(keep)[0].tolist())
+            assert all(s2r[r2s[row]] == row for row in range(len(r2s)))
+            assert np.array_equal(d["send_buf"], x[r2s // k])
+            assert len(co) == len(chunks) + G + 1 and co[0] == 0 and co[-1] == len(r2s)
+            got = {g: [] for g in range(G)}
+            for c, (dest, rows) in enumerate(chunks + [(g, None) for g in range(G)]):
+                part = r2s[co[c]:co[c + 1]].tolist()
+                if not (0 <= dest < G):
+                    assert part == []
+                    continue
+                assert all(e2g[flat[s]] == dest for s in part)              # a chunk has one destination
+                if rows is not None:
+                    assert len(part) <= rows
+                    # a planned chunk is short only when its destination has run out
+                    assert len(part) == rows or len(got[dest]) + len(part) == len(whole[dest])
+                got[dest].extend(part)
+            assert got == whole                                             # chunks of a destination, joined, are its sequence
+            po, pe = d["piece_offset"], d["piece_expert"]
+            assert po[0] == 0 and po[-1] == len(r2s) and len(po) == len(pe) + 1
+            assert np.all(np.diff(po) > 0)
+            cuts = set(co.tolist())
+            for i, e in enumerate(pe):
+                assert np.all(flat[r2s[po[i]:po[i + 1]]] == e)
+                assert not any(po[i] < c < po[i + 1] for c in cuts)            # a piece never straddles a chunk
+                if i + 1 < len(pe):
+                    assert pe[i + 1] != e or po[i + 1] in cuts                 # maximal: a new piece needs a reason
+
+
 # ------------------------------------------------------------------ FFN
 def test_ffn_special_cases():
     r = rng(8)

@@ -85,6 +85,35 @@ def test_padding_and_round_invariants(hetero):
             assert sent == P                                                # everything delivered once
 
 
+@pytest.mark.parametrize("hetero", [False, True])
+def test_chunk_lists_follow_the_rounds(hetero):
+    r = np.random.default_rng(41)
+    for n in (2, 3, 5, 8):
+        for _ in range(4):
+            D = random_D(r, n)
+            B = list(r.choice([1.0, 0.8, 0.5, 0.4], size=n)) if hetero else None
+            rnds, bm = S.rounds(D, B)
+            per_round_receivers = [dict() for _ in rnds]
+            for g in range(n):
+                chunks, which = S.chunks_from_rounds(D, B, g)
+                assert which == sorted(which) and len(set(which)) == len(which)    # at most one chunk per round
+                got = [0] * n
+                for (j, rows), rr in zip(chunks, which):
+                    dst, tau, real = rnds[rr]
+                    assert j == dst[g] and j != g and rows > 0
+                    rate = Fraction(1) if B is None else min(Fraction(B[g]), Fraction(B[j]))
+                    assert rows < tau * rate + 1                                    # fits the round, up to one token of rounding
+                    got[j] += rows
+                    assert per_round_receivers[rr].setdefault(j, g) == g            # nobody else sends to j in that round
+                assert got == [0 if j == g else D[g][j] for j in range(n)]          # every token exactly once
+            if not hetero:
+                # integer traffic on unit links: rounds have whole durations and a chunk is exactly its round's share
+                for g in range(n):
+                    chunks, which = S.chunks_from_rounds(D, B, g)
+                    for (j, rows), rr in zip(chunks, which):
+                        assert rows == rnds[rr][2][g]
+
+
 def test_bmax_is_a_lower_bound_and_brute_force_meets_it_when_unit_flows():
     r = np.random.default_rng(32)
     for n in (3, 4):
