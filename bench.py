@@ -119,6 +119,16 @@ def build_workload(cfg, torch, P, W):
     b_ffn = P.bind_expert_ffn(recv, R, ffn_off, ffn_exp, len(exp), table, H, F, cfg.act, cfg.dtype, ffn_out, ws)
     b_combine = P.bind_combine(ctx, ret, s2r, w, None, y)
 
+    # the same send buffer laid out for the preemptive plan of the schedule's rounds: timed beside the
+    # stages for information, not part of the step (it writes buffers of its own)
+    chunks = P.aurora_chunks(D, rates, g)
+    chunk_plan = P.MoeChunkPlan(ctx, e2g, chunks)
+    nc = len(chunks) + G
+    c_send = torch.zeros((S, H), dtype=tdt, device=dev)
+    c_s2r, c_r2s = torch.zeros(S, **i32), torch.zeros(S, **i32)
+    c_off, p_off, p_exp, n_pieces = torch.zeros(nc + 1, **i32), torch.zeros(nc + E + 1, **i32), torch.zeros(nc + E, **i32), torch.zeros(1, **i32)
+    b_dispatch_chunks = P.bind_dispatch_chunks(ctx, chunk_plan, x, idx, c_send, c_s2r, c_r2s, c_off, p_off, p_exp, n_pieces)
+
     def cur():
         return torch.cuda.current_stream().cuda_stream
 
@@ -135,7 +145,8 @@ def build_workload(cfg, torch, P, W):
         b_combine(st)
 
     stages = {"route": lambda: b_route(cur()), "traffic": lambda: b_traffic(cur()), "dispatch": lambda: b_dispatch(cur()),
-              "expert_ffn": lambda: b_ffn(cur()), "combine": lambda: b_combine(cur())}
+              "expert_ffn": lambda: b_ffn(cur()), "combine": lambda: b_combine(cur()),
+              "dispatch_chunks (not in the step)": lambda: b_dispatch_chunks(cur())}
     ffn_timed = lambda: P.moe_expert_ffn_timed(recv, R, ffn_off, ffn_exp, len(exp), table, H, F, cfg.act, cfg.dtype,
                                                ffn_out, ws)
     n_kept = int(so[-1])
@@ -143,7 +154,7 @@ def build_workload(cfg, torch, P, W):
                 idx=idx, w=w, expert_count=expert_count, dest_count=dest_count, n_dropped=n_dropped,
                 send_buf=send_buf, slot_to_row=s2r, row_to_slot=r2s, seg_offset=seg_offset, seg_expert=seg_expert,
                 recv=recv, ffn_out=ffn_out, ret=ret, ffn_off=off, ffn_exp=exp, local=local, dest_order=dest_order,
-                self_spans=self_spans, keep=(ctx, x, wg, bias, experts, table, ws))
+                self_spans=self_spans, n_chunks=len(chunks), keep=(ctx, x, wg, bias, experts, table, ws, chunk_plan))
 
 
 def capture(torch, fn, reps=1):

@@ -126,6 +126,33 @@ int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* topk_idx, const int
                  const int32_t* dest_order, void* send_buf, int32_t* slot_to_row,
                  int32_t* row_to_slot, int32_t* seg_offset, int32_t* seg_expert, void* stream);
 
+/* A preemptive send plan (Appendix A; see aurora_chunks): chunk c carries the
+ * next chunk_rows[c] slots of destination chunk_dest[c].  The slots of a
+ * destination form one sequence - expert by expert (ascending id), inside an
+ * expert by ascending slot id, the order moe_dispatch uses - and a chunk gets
+ * fewer slots (possibly none) when the sequence runs out; a chunk whose dest is
+ * no GPU stays empty; negative row counts count as 0.  Whatever the plan does not
+ * cover follows after the last chunk, one left-over chunk per destination in
+ * ascending GPU id (so the plan may come from historical statistics, Sec. 2.4).
+ *   expert_to_gpu HOST [E]; chunk_dest, chunk_rows HOST [n_chunks], n_chunks <= 4096
+ * The plan owns device tables that a dispatch rewrites: dispatches that share a
+ * plan must not overlap.  Creation and destruction synchronise with the device. */
+typedef struct moe_chunk_plan moe_chunk_plan;
+int moe_chunk_plan_create(moe_ctx* ctx, const int32_t* expert_to_gpu, int32_t n_chunks, const int32_t* chunk_dest,
+                          const int32_t* chunk_rows, moe_chunk_plan** out);
+int moe_chunk_plan_destroy(moe_chunk_plan* plan);
+
+/* moe_dispatch for a preemptive plan: the send buffer is the chunks in plan
+ * order, then the left-over chunks.  With nc = n_chunks + G:
+ *   chunk_offset  device [nc+1] out: first send row of each chunk, then the row count
+ *   piece_offset  device [nc+E+1] out, piece_expert device [nc+E] out, n_pieces device [1] out:
+ *                 a piece is a maximal run of rows of one chunk and one expert, listed in
+ *                 buffer order; piece_offset[n_pieces] is the row count
+ * Other arguments, context caching and error behaviour as for moe_dispatch. */
+int moe_dispatch_chunks(moe_ctx* ctx, const moe_chunk_plan* plan, const void* x, const int32_t* topk_idx,
+                        void* send_buf, int32_t* slot_to_row, int32_t* row_to_slot, int32_t* chunk_offset,
+                        int32_t* piece_offset, int32_t* piece_expert, int32_t* n_pieces, void* stream);
+
 /* One expert's weights, stored [out,in] row-major in `dtype`, device memory. */
 typedef struct {
     const void* w1;     /* [F,H]: the only up-projection (MLP) or the gate projection (SwiGLU) */
@@ -205,6 +232,16 @@ typedef struct {
  * earliest gap free at both ends). */
 int aurora_order(int32_t n, const int64_t* D, const double* B, aurora_schedule* out);
 void aurora_schedule_free(aurora_schedule* s);
+
+/* The send plan of GPU g under the rounds of `s` (Appendix A: in every time slot a
+ * GPU sends to one GPU; a flow may be served in several slots): one chunk per
+ * round in which g sends real traffic, in round order.  A chunk carries whole
+ * tokens: the cumulative amount sent to that destination by the end of the
+ * round, rounded down, minus what earlier chunks carried; the counts of a
+ * destination add up to d_g,dest.  D and B must be the ones `s` was made from.
+ *   chunk_dest, chunk_rows  HOST [s->n_rounds] out     n_chunks  HOST [1] out */
+int aurora_chunks(const aurora_schedule* s, const int64_t* D, const double* B, int32_t g, int32_t* chunk_dest,
+                  int32_t* chunk_rows, int32_t* n_chunks);
 
 /* Completion time of the all-to-all on the big-switch model (Sec. 2.4) when GPU
  * i sends to order[i*n .. i*n+n) one destination after another; a receiver with

@@ -33,6 +33,9 @@ SIGNATURES = {
     "moe_route": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "moe_traffic": (C.c_int, [_vp, _vp, C.POINTER(_i32), _vp, _vp, _vp, _vp]),
     "moe_dispatch": (C.c_int, [_vp, _vp, _vp, C.POINTER(_i32), C.POINTER(_i32), _vp, _vp, _vp, _vp, _vp, _vp]),
+    "moe_chunk_plan_create": (C.c_int, [_vp, C.POINTER(_i32), _i32, C.POINTER(_i32), C.POINTER(_i32), C.POINTER(_vp)]),
+    "moe_chunk_plan_destroy": (C.c_int, [_vp]),
+    "moe_dispatch_chunks": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "moe_ffn_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32, _i32]),
     "moe_expert_ffn": (C.c_int, [_vp, _i32, _vp, _vp, _i32, C.POINTER(moe_expert_w), _i32, _i32, _i32, _i32, _i32,
                                  _vp, _vp, _sz, _vp]),
@@ -41,6 +44,8 @@ SIGNATURES = {
     "moe_combine": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "aurora_order": (C.c_int, [_i32, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(aurora_schedule)]),
     "aurora_schedule_free": (None, [C.POINTER(aurora_schedule)]),
+    "aurora_chunks": (C.c_int, [C.POINTER(aurora_schedule), C.POINTER(C.c_int64), C.POINTER(C.c_double), _i32,
+                                C.POINTER(_i32), C.POINTER(_i32), C.POINTER(_i32)]),
     "aurora_simulate": (C.c_int, [_i32, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(_i32),
                                   C.POINTER(C.c_double)]),
     "colocate_match": (C.c_int, [_i32, _i32, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(_i32),

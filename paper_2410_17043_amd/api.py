@@ -151,6 +151,47 @@ def moe_dispatch(ctx, x, topk_idx, expert_to_gpu, dest_order, send_buf, slot_to_
                                                 _ptr(seg_expert), _stream()))
 
 
+class MoeChunkPlan:
+    """Owner of a moe_chunk_plan: a preemptive send plan [(dest, rows), ...] for one GPU."""
+
+    def __init__(self, ctx, expert_to_gpu, chunks):
+        self.ctx, self.lib = ctx, ctx.lib
+        self.n_chunks = len(chunks)
+        _a, e2g = _i32_array(expert_to_gpu)
+        _d, dest = _i32_array([c[0] for c in chunks] or [0])
+        _r, rows = _i32_array([c[1] for c in chunks] or [0])
+        self.handle = C.c_void_p()
+        _check("moe_chunk_plan_create", self.lib.moe_chunk_plan_create(ctx.handle, e2g, self.n_chunks, dest, rows,
+                                                                       C.byref(self.handle)))
+
+    def close(self):
+        if self.handle:
+            self.lib.moe_chunk_plan_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def moe_dispatch_chunks(ctx, plan, x, topk_idx, send_buf, slot_to_row, row_to_slot, chunk_offset, piece_offset,
+                        piece_expert, n_pieces):
+    _check("moe_dispatch_chunks", ctx.lib.moe_dispatch_chunks(
+        ctx.handle, plan.handle, _ptr(x), _ptr(topk_idx), _ptr(send_buf), _ptr(slot_to_row), _ptr(row_to_slot),
+        _ptr(chunk_offset), _ptr(piece_offset), _ptr(piece_expert), _ptr(n_pieces), _stream()))
+
+
+def bind_dispatch_chunks(ctx, plan, x, topk_idx, send_buf, slot_to_row, row_to_slot, chunk_offset, piece_offset,
+                         piece_expert, n_pieces):
+    return Bound(ctx.lib.moe_dispatch_chunks, "moe_dispatch_chunks",
+                 (ctx.handle, plan.handle, _ptr(x), _ptr(topk_idx), _ptr(send_buf), _ptr(slot_to_row), _ptr(row_to_slot),
+                  _ptr(chunk_offset), _ptr(piece_offset), _ptr(piece_expert), _ptr(n_pieces), _stream()),
+                 (ctx, plan, x, topk_idx, send_buf, slot_to_row, row_to_slot, chunk_offset, piece_offset, piece_expert,
+                  n_pieces), 11)
+
+
 def moe_ffn_workspace_bytes(R_max, H, F, act, dtype):
     return int(_lib.load().moe_ffn_workspace_bytes(R_max, H, F, act, _DT[dtype]))
 
@@ -223,6 +264,24 @@ def aurora_order(D, B=None):
     finally:
         lib.aurora_schedule_free(C.byref(s))
     return out
+
+
+def aurora_chunks(D, B, g):
+    """Plan the all-to-all and return GPU g's chunk list [(dest, rows), ...] under its rounds."""
+    lib = _lib.load()
+    Dm, Dp = _i64_matrix(D)
+    n = Dm.shape[0]
+    _Bm, Bp = _f64_array(B)
+    s = aurora_schedule()
+    _check("aurora_order", lib.aurora_order(n, Dp, Bp, C.byref(s)))
+    try:
+        dest = (C.c_int32 * max(s.n_rounds, 1))()
+        rows = (C.c_int32 * max(s.n_rounds, 1))()
+        nc = C.c_int32()
+        _check("aurora_chunks", lib.aurora_chunks(C.byref(s), Dp, Bp, g, dest, rows, C.byref(nc)))
+        return [(int(dest[i]), int(rows[i])) for i in range(nc.value)]
+    finally:
+        lib.aurora_schedule_free(C.byref(s))
 
 
 def aurora_simulate(D, B, order):

@@ -19,6 +19,9 @@
 // ranks, writes slot_to_row / row_to_slot, reads the token row once and writes it to the
 // rows of its kept slots (16-byte lanes, 1 KB per wave access, streaming loads/stores).
 #include "common.h"
+#include <algorithm>
+#include <new>
+#include <vector>
 
 namespace {
 
@@ -232,6 +235,37 @@ __global__ __launch_bounds__(1024) void small_rank_kernel(const int32_t* __restr
     traffic_outputs(raw, kept, E, G, capacity, map, expert_count, dest_count, n_dropped);
 }
 
+// Writes the token row at `src` (its first 4 KB already requested into v) to the send rows of the
+// token's k slots; lane j < k holds the row of slot j in my_row (-1: dropped).
+template <int K>
+__device__ __forceinline__ void copy_token_rows(const u32x4* __restrict__ src, u32x4 (&v)[4], int my_row, int k, int row16,
+                                                u32x4* __restrict__ send_buf, int lane) {
+    constexpr int KM = (K > 0) ? K : MOE_MAX_K;
+    int rows[KM];
+#pragma unroll
+    for (int j = 0; j < KM; ++j) rows[j] = (j < k) ? __shfl(my_row, j, 64) : -1;
+    for (int c0 = 0; c0 < row16; c0 += 256) {
+        if (c0 > 0) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int c = c0 + u * 64 + lane;
+                if (c < row16) v[u] = __builtin_nontemporal_load(src + c);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < KM; ++j) {
+            if (rows[j] >= 0) {
+                u32x4* dst = send_buf + (size_t)rows[j] * row16;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int c = c0 + u * 64 + lane;
+                    if (c < row16) __builtin_nontemporal_store(v[u], dst + c);
+                }
+            }
+        }
+    }
+}
+
 // One wave per token.  row16 = 16-byte units per row.
 template <int K>
 __global__ __launch_bounds__(256) void scatter_kernel(const u32x4* __restrict__ x, const int32_t* __restrict__ idx,
@@ -322,30 +356,164 @@ __global__ __launch_bounds__(256) void scatter_kernel(const u32x4* __restrict__ 
         }
         slot_to_row[s] = my_row;
     }
-    constexpr int KM = (K > 0) ? K : MOE_MAX_K;
-    int rows[KM];
+    copy_token_rows<K>(src, v, my_row, k, row16, send_buf, lane);
+}
+
+// ------------------------------------------------------------------------------ chunked layout
+// Send buffer for a preemptive schedule (Appendix A): the slots of a destination form one sequence
+// (expert by expert, then slot order) that is cut into the plan's chunks; the buffer is the chunks
+// in plan order, then one left-over chunk per destination.  Everything that depends only on the
+// plan is tabulated on the host when the plan is created; a dispatch computes, from the actual
+// per-expert counts, where each chunk starts (one block), and the scatter kernel finds the chunk
+// of a slot by binary search among its destination's chunks.
+constexpr int kMaxPlanChunks = 4096;
+constexpr int kMaxChunks = kMaxPlanChunks + MOE_MAX_G;      // plus one left-over chunk per destination
+constexpr int kLayoutThreads = 1024;
+constexpr int kChunksPerThread = (kMaxChunks + kLayoutThreads - 1) / kLayoutThreads;
+
+struct ChunkTables {                  // device pointers
+    int nc;                           // chunks in all (plan + G left-over)
+    const int32_t* c_dest;            // [nc] destination, -1: no GPU (always empty)
+    const int32_t* c_cumlo;           // [nc] planned slots of the destination before this chunk
+    const int32_t* c_cumhi;           // [nc] ... after it; INT_MAX for a left-over chunk
+    const int32_t* p_chunk;           // [np] chunk ids grouped by destination, in plan order inside a group
+    const int32_t* p_cumhi;           // [np] c_cumhi of p_chunk
+    const int32_t* p_begin;           // [G+1] group of destination d is [p_begin[d], p_begin[d+1])
+    int32_t* c_row0;                  // [nc+1] written per dispatch: first send row of each chunk
+    int32_t* expert_first;            // [E] written per dispatch: position of the expert's first slot in its destination's sequence
+};
+
+// Exclusive prefix sum over one value per thread, 1024 threads; returns the total to every thread.
+__device__ __forceinline__ int block_exclusive_scan(int v, int* excl_out, int* wave_tot /* LDS [16] */) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int incl = v;
 #pragma unroll
-    for (int j = 0; j < KM; ++j) rows[j] = (j < k) ? __shfl(my_row, j, 64) : -1;
-    for (int c0 = 0; c0 < row16; c0 += 256) {
-        if (c0 > 0) {
+    for (int o = 1; o < 64; o <<= 1) {
+        const int up = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += up;
+    }
+    __syncthreads();                                          // wave_tot may still be read from an earlier scan
+    if (lane == 63) wave_tot[wave] = incl;
+    __syncthreads();
+    int before = 0, total = 0;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int c = c0 + u * 64 + lane;
-                if (c < row16) v[u] = __builtin_nontemporal_load(src + c);
+    for (int w = 0; w < kLayoutThreads / 64; ++w) {
+        const int t = wave_tot[w];
+        if (w < wave) before += t;
+        total += t;
+    }
+    *excl_out = before + incl - v;
+    return total;
+}
+
+__global__ __launch_bounds__(kLayoutThreads) void chunk_layout_kernel(ChunkTables tb, const int32_t* __restrict__ raw_count,
+                                                                      int E, int G, int capacity, SegMap map,
+                                                                      int32_t* __restrict__ chunk_offset,
+                                                                      int32_t* __restrict__ piece_offset,
+                                                                      int32_t* __restrict__ piece_expert,
+                                                                      int32_t* __restrict__ n_pieces) {
+    __shared__ int kept[MOE_MAX_E], first[MOE_MAX_E], dest_cnt[MOE_MAX_G], wave_tot[kLayoutThreads / 64];
+    const int tid = threadIdx.x;
+    if (tid < E) {
+        const int c = raw_count[tid];
+        kept[tid] = (capacity > 0 && c > capacity) ? capacity : c;
+    }
+    __syncthreads();
+    if (tid < G) {                                            // thread d walks the experts of destination d in id order
+        int run = 0;
+        for (int e = 0; e < E; ++e)
+            if (map.expert_gpu[e] == tid) { first[e] = run; run += kept[e]; }
+        dest_cnt[tid] = run;
+    }
+    __syncthreads();
+    if (tid < E) tb.expert_first[tid] = first[tid];
+    // thread t owns chunks [t * CPT, (t + 1) * CPT): sizes, then the block-wide prefix
+    const int c0 = tid * kChunksPerThread;
+    int size[kChunksPerThread], pieces[kChunksPerThread], sum = 0, psum = 0;
+#pragma unroll
+    for (int u = 0; u < kChunksPerThread; ++u) {
+        const int c = c0 + u;
+        size[u] = 0; pieces[u] = 0;
+        if (c < tb.nc) {
+            const int d = tb.c_dest[c];
+            if (d >= 0) {
+                const int lo = min(tb.c_cumlo[c], dest_cnt[d]), hi = min(tb.c_cumhi[c], dest_cnt[d]);
+                size[u] = hi - lo;
+                if (hi > lo)
+                    for (int e = 0; e < E; ++e)               // experts of d whose slots meet [lo, hi)
+                        if (map.expert_gpu[e] == d && first[e] < hi && first[e] + kept[e] > lo) ++pieces[u];
             }
         }
+        sum += size[u];
+        psum += pieces[u];
+    }
+    int row0, piece0;
+    const int total = block_exclusive_scan(sum, &row0, wave_tot);
+    const int total_pieces = block_exclusive_scan(psum, &piece0, wave_tot);
 #pragma unroll
-        for (int j = 0; j < KM; ++j) {
-            if (rows[j] >= 0) {
-                u32x4* dst = send_buf + (size_t)rows[j] * row16;
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int c = c0 + u * 64 + lane;
-                    if (c < row16) __builtin_nontemporal_store(v[u], dst + c);
-                }
+    for (int u = 0; u < kChunksPerThread; ++u) {
+        const int c = c0 + u;
+        if (c < tb.nc) {
+            tb.c_row0[c] = row0;
+            chunk_offset[c] = row0;
+            if (size[u] > 0) {
+                const int d = tb.c_dest[c];
+                const int lo = min(tb.c_cumlo[c], dest_cnt[d]), hi = lo + size[u];
+                for (int e = 0; e < E; ++e)
+                    if (map.expert_gpu[e] == d && first[e] < hi && first[e] + kept[e] > lo) {
+                        piece_offset[piece0] = row0 + max(first[e], lo) - lo;
+                        piece_expert[piece0] = e;
+                        ++piece0;
+                    }
             }
+            row0 += size[u];
         }
     }
+    if (tid == 0) {
+        tb.c_row0[tb.nc] = total;
+        chunk_offset[tb.nc] = total;
+        piece_offset[total_pieces] = total;
+        *n_pieces = total_pieces;
+    }
+}
+
+// One wave per token, like scatter_kernel; the send row of a kept slot comes from the chunk tables.
+template <int K>
+__global__ __launch_bounds__(256) void scatter_chunks_kernel(const u32x4* __restrict__ x, const int32_t* __restrict__ idx,
+                                                             const int32_t* __restrict__ slot_rank, int T, int k_rt, int E,
+                                                             int capacity, SegMap map, ChunkTables tb, int row16,
+                                                             u32x4* __restrict__ send_buf, int32_t* __restrict__ slot_to_row,
+                                                             int32_t* __restrict__ row_to_slot) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int t = blockIdx.x * 4 + wave;
+    const int k = (K > 0) ? K : k_rt;
+    if (t >= T) return;
+    const u32x4* src = x + (size_t)t * row16;
+    u32x4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int c = u * 64 + lane;
+        if (c < row16) v[u] = __builtin_nontemporal_load(src + c);
+    }
+    int my_row = -1;
+    if (lane < k) {
+        const int s = t * k + lane;
+        const int e = idx[s], rank = slot_rank[s];
+        if (e >= 0 && e < E && rank >= 0 && (capacity <= 0 || rank < capacity)) {
+            const int d = map.expert_gpu[e];
+            const int q = tb.expert_first[e] + rank;          // position in the destination's sequence
+            int lo = tb.p_begin[d], hi = tb.p_begin[d + 1] - 1;   // the last one is the left-over chunk: q < INT_MAX
+            while (lo < hi) {                                 // first chunk of d with q < cumhi
+                const int mid = (lo + hi) >> 1;
+                if (q < tb.p_cumhi[mid]) hi = mid; else lo = mid + 1;
+            }
+            const int c = tb.p_chunk[lo];
+            my_row = tb.c_row0[c] + q - tb.c_cumlo[c];
+            row_to_slot[my_row] = s;
+        }
+        slot_to_row[s] = my_row;
+    }
+    copy_token_rows<K>(src, v, my_row, k, row16, send_buf, lane);
 }
 
 int build_segmap(const moe_shape& s, const int32_t* expert_to_gpu, const int32_t* dest_order, SegMap* m) {
@@ -432,5 +600,117 @@ extern "C" int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* topk_idx
     else MOE_SCATTER(0);
 #undef MOE_SCATTER
     MOE_LAUNCH_CHECK("scatter_kernel");
+    return MOE_OK;
+}
+
+struct moe_chunk_plan {
+    SegMap map;
+    ChunkTables tb;
+    int32_t E, G, n_chunks;
+    int32_t* dev;                      // one allocation behind all the tables
+};
+
+extern "C" int moe_chunk_plan_create(moe_ctx* ctx, const int32_t* expert_to_gpu, int32_t n_chunks, const int32_t* chunk_dest,
+                                     const int32_t* chunk_rows, moe_chunk_plan** out) {
+    if (!ctx || !expert_to_gpu || !out || (n_chunks > 0 && (!chunk_dest || !chunk_rows)))
+        return moe_set_error(MOE_EINVAL, "moe_chunk_plan_create: NULL argument");
+    if (n_chunks < 0 || n_chunks > kMaxPlanChunks)
+        return moe_set_error(MOE_ESHAPE, "moe_chunk_plan_create: n_chunks = %d outside [0, %d]", n_chunks, kMaxPlanChunks);
+    const moe_shape& s = ctx->s;
+    moe_chunk_plan* p = new (std::nothrow) moe_chunk_plan;
+    if (!p) return moe_set_error(MOE_ENOMEM, "moe_chunk_plan_create: out of host memory");
+    int rc = build_segmap(s, expert_to_gpu, nullptr, &p->map);
+    if (rc != MOE_OK) { delete p; return rc; }
+    const int G = s.G, nc = n_chunks + G;
+    std::vector<int32_t> c_dest(nc), c_cumlo(nc), c_cumhi(nc), p_chunk, p_cumhi, p_begin(G + 1);
+    std::vector<int64_t> planned(G, 0);
+    for (int c = 0; c < nc; ++c) {
+        const bool left_over = c >= n_chunks;
+        const int d = left_over ? c - n_chunks : chunk_dest[c];
+        if (d < 0 || d >= G) { c_dest[c] = -1; c_cumlo[c] = c_cumhi[c] = 0; continue; }
+        const int64_t rows = left_over ? (int64_t)INT32_MAX : (chunk_rows[c] > 0 ? chunk_rows[c] : 0);
+        c_dest[c] = d;
+        c_cumlo[c] = (int32_t)std::min<int64_t>(planned[d], INT32_MAX);
+        planned[d] = std::min<int64_t>(planned[d] + rows, INT32_MAX);
+        c_cumhi[c] = (int32_t)planned[d];
+    }
+    for (int d = 0; d < G; ++d) {
+        p_begin[d] = (int32_t)p_chunk.size();
+        for (int c = 0; c < nc; ++c)
+            if (c_dest[c] == d) { p_chunk.push_back(c); p_cumhi.push_back(c_cumhi[c]); }
+    }
+    p_begin[G] = (int32_t)p_chunk.size();
+    const int np = (int)p_chunk.size();
+    // device layout: c_dest | c_cumlo | c_cumhi | p_chunk | p_cumhi | p_begin | c_row0 | expert_first
+    const size_t n_static = (size_t)3 * nc + 2 * np + (G + 1);
+    const size_t n_all = n_static + (nc + 1) + s.E;
+    std::vector<int32_t> host(n_static);
+    size_t o = 0;
+    auto put = [&](const std::vector<int32_t>& v, size_t n) { std::copy(v.begin(), v.begin() + n, host.begin() + o); o += n; };
+    put(c_dest, nc); put(c_cumlo, nc); put(c_cumhi, nc); put(p_chunk, np); put(p_cumhi, np); put(p_begin, G + 1);
+    hipError_t e = hipMalloc((void**)&p->dev, n_all * sizeof(int32_t));
+    if (e != hipSuccess) {
+        delete p;
+        return moe_set_error(e == hipErrorOutOfMemory ? MOE_ENOMEM : MOE_EHIP, "hipMalloc(%zu): %s", n_all * sizeof(int32_t), hipGetErrorString(e));
+    }
+    e = hipMemcpy(p->dev, host.data(), n_static * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        (void)hipFree(p->dev);
+        delete p;
+        return moe_set_error(MOE_EHIP, "hipMemcpy: %s", hipGetErrorString(e));
+    }
+    int32_t* d = p->dev;
+    p->tb.nc = nc;
+    p->tb.c_dest = d; d += nc;
+    p->tb.c_cumlo = d; d += nc;
+    p->tb.c_cumhi = d; d += nc;
+    p->tb.p_chunk = d; d += np;
+    p->tb.p_cumhi = d; d += np;
+    p->tb.p_begin = d; d += G + 1;
+    p->tb.c_row0 = d; d += nc + 1;
+    p->tb.expert_first = d;
+    p->E = s.E; p->G = G; p->n_chunks = n_chunks;
+    *out = p;
+    return MOE_OK;
+}
+
+extern "C" int moe_chunk_plan_destroy(moe_chunk_plan* plan) {
+    if (!plan) return MOE_OK;
+    hipError_t e = hipFree(plan->dev);
+    delete plan;
+    if (e != hipSuccess) return moe_set_error(MOE_EHIP, "hipFree: %s", hipGetErrorString(e));
+    return MOE_OK;
+}
+
+extern "C" int moe_dispatch_chunks(moe_ctx* ctx, const moe_chunk_plan* plan, const void* x, const int32_t* topk_idx,
+                                   void* send_buf, int32_t* slot_to_row, int32_t* row_to_slot, int32_t* chunk_offset,
+                                   int32_t* piece_offset, int32_t* piece_expert, int32_t* n_pieces, void* stream) {
+    if (!ctx || !plan || !x || !topk_idx || !send_buf || !slot_to_row || !row_to_slot || !chunk_offset || !piece_offset ||
+        !piece_expert || !n_pieces)
+        return moe_set_error(MOE_EINVAL, "moe_dispatch_chunks: NULL argument");
+    if (!aligned16(x) || !aligned16(send_buf))
+        return moe_set_error(MOE_EALIGN, "moe_dispatch_chunks: x and send_buf must be 16-byte aligned");
+    const moe_shape& s = ctx->s;
+    if (plan->E != s.E || plan->G != s.G) return moe_set_error(MOE_ESHAPE, "moe_dispatch_chunks: plan made for another shape");
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (ctx->rank_src != topk_idx) {                     // no fresh ranks for these indices: compute them now
+        int rc = launch_rank_pass(ctx, topk_idx, plan->map, nullptr, nullptr, nullptr, st);
+        if (rc != MOE_OK) return rc;
+    }
+    hipLaunchKernelGGL(chunk_layout_kernel, dim3(1), dim3(kLayoutThreads), 0, st, plan->tb, ctx->raw_count, s.E, s.G,
+                       s.capacity, plan->map, chunk_offset, piece_offset, piece_expert, n_pieces);
+    MOE_LAUNCH_CHECK("chunk_layout_kernel");
+    const int row16 = (int)((int64_t)s.H * elem_size(s.dtype) / 16);
+    const dim3 grid((s.T + 3) / 4);
+    const u32x4* xs = reinterpret_cast<const u32x4*>(x);
+    u32x4* sb = reinterpret_cast<u32x4*>(send_buf);
+#define MOE_SCATTER(KK)                                                                                              \
+    hipLaunchKernelGGL(scatter_chunks_kernel<KK>, grid, dim3(256), 0, st, xs, topk_idx, ctx->slot_rank, s.T, s.k, s.E, \
+                       s.capacity, plan->map, plan->tb, row16, sb, slot_to_row, row_to_slot)
+    if (s.k == 1) MOE_SCATTER(1);
+    else if (s.k == 2) MOE_SCATTER(2);
+    else MOE_SCATTER(0);
+#undef MOE_SCATTER
+    MOE_LAUNCH_CHECK("scatter_chunks_kernel");
     return MOE_OK;
 }

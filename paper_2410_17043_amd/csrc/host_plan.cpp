@@ -338,6 +338,50 @@ extern "C" int aurora_order(int32_t n, const int64_t* D, const double* B, aurora
     return MOE_OK;
 }
 
+extern "C" int aurora_chunks(const aurora_schedule* s, const int64_t* D, const double* B, int32_t g, int32_t* chunk_dest,
+                             int32_t* chunk_rows, int32_t* n_chunks) {
+    if (!s || !chunk_dest || !chunk_rows || !n_chunks) return moe_set_error(MOE_EINVAL, "aurora_chunks: NULL argument");
+    const int n = s->n;
+    int rc = check_traffic("aurora_chunks", n, D, B);
+    if (rc != MOE_OK) return rc;
+    if (g < 0 || g >= n) return moe_set_error(MOE_ESHAPE, "aurora_chunks: g = %d outside [0, %d)", g, n);
+    if (!s->dst || !s->duration) return moe_set_error(MOE_EINVAL, "aurora_chunks: schedule holds no rounds");
+    // Per destination: scaled real traffic not yet sent, tokens already put into chunks, last chunk.
+    double left[MOE_MAX_G], total[MOE_MAX_G], rate[MOE_MAX_G];
+    int64_t sent[MOE_MAX_G];
+    int last[MOE_MAX_G];
+    for (int j = 0; j < n; ++j) {
+        rate[j] = B ? std::min(B[g], B[j]) : 1.0;
+        total[j] = (j == g) ? 0.0 : (double)D[(size_t)g * n + j] / rate[j];
+        left[j] = total[j];
+        sent[j] = 0;
+        last[j] = -1;
+    }
+    int nc = 0;
+    for (int r = 0; r < s->n_rounds; ++r) {
+        const int j = s->dst[(size_t)r * n + g];
+        if (j < 0 || j >= n || j == g) continue;
+        left[j] -= std::min(left[j], s->duration[r]);        // real traffic first, as in the rounds themselves
+        int64_t cum = (int64_t)std::floor((total[j] - left[j]) * rate[j] + 1e-6);
+        cum = std::min<int64_t>(cum, D[(size_t)g * n + j]);
+        if (cum > sent[j]) {
+            chunk_dest[nc] = j;
+            chunk_rows[nc] = (int32_t)(cum - sent[j]);
+            last[j] = nc++;
+            sent[j] = cum;
+        }
+    }
+    for (int j = 0; j < n; ++j) {                            // whatever floating point left over joins the last chunk
+        const int64_t miss = (j == g) ? 0 : D[(size_t)g * n + j] - sent[j];
+        if (miss > 0) {
+            if (last[j] < 0) return moe_set_error(MOE_ESHAPE, "aurora_chunks: the schedule never sends %d -> %d; made from another matrix?", g, j);
+            chunk_rows[last[j]] += (int32_t)miss;
+        }
+    }
+    *n_chunks = nc;
+    return MOE_OK;
+}
+
 extern "C" int aurora_simulate(int32_t n, const int64_t* D, const double* B, const int32_t* order, double* time_out) {
     if (!order || !time_out) return moe_set_error(MOE_EINVAL, "aurora_simulate: NULL argument");
     int rc = check_traffic("aurora_simulate", n, D, B);

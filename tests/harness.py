@@ -77,14 +77,16 @@ def rel_err(got, ref):
     return float(np.max(np.abs(np.asarray(got, dtype=np.float64) - ref)) / max(np.max(np.abs(ref)), 1e-300))
 
 
-def run_emulated_cluster(cfg, dest_orders=None, n_shared=0):
+def run_emulated_cluster(cfg, dest_orders=None, n_shared=0, chunked=False):
     """The whole layer over cfg.G simulated GPUs on the one real GPU.
 
     Every simulated GPU runs route / traffic / dispatch through the library; the two
     all-to-alls are plain device copies of whole segments (they stand in for the wire);
     each simulated GPU then runs the grouped FFN over what it received, results travel
-    back to the rows they came from, and combine forms y.  Returns the per-GPU inputs,
-    the measured traffic matrix and y per GPU (host arrays).
+    back to the rows they came from, and combine forms y.  With ``chunked`` the send
+    buffers follow the preemptive plan of the library's rounds (moe_dispatch_chunks) and
+    the pieces of the chunks travel instead of whole segments.  Returns the per-GPU
+    inputs, the measured traffic matrix and y per GPU (host arrays).
     """
     G, E, H_, F = cfg.G, cfg.E, cfg.H, cfg.F
     inputs = [W.make_layer_inputs(cfg, g) for g in range(G)]
@@ -107,10 +109,25 @@ def run_emulated_cluster(cfg, dest_orders=None, n_shared=0):
         xs.append(x)
     if dest_orders is None:
         dest_orders = P.aurora_order(D)["dest_order"]          # offline plan from the measured statistics
-    for g in range(G):
-        shares[g].dispatch(xs[g], e2g, dest_orders[g])
-    torch.cuda.synchronize()
-    seg = [(host(sh.seg_offset), host(sh.seg_expert)) for sh in shares]
+    if chunked:
+        seg = []
+        for g in range(G):
+            chunks = P.aurora_chunks(D, None, g)
+            plan = P.MoeChunkPlan(shares[g].ctx, e2g, chunks)
+            nc = len(chunks) + G
+            i32 = dict(dtype=torch.int32, device=DEV)
+            co, po, pe = torch.zeros(nc + 1, **i32), torch.zeros(nc + E + 1, **i32), torch.zeros(nc + E, **i32)
+            m = torch.zeros(1, **i32)
+            sh = shares[g]
+            P.moe_dispatch_chunks(sh.ctx, plan, xs[g], sh.idx, sh.send_buf, sh.slot_to_row, sh.row_to_slot, co, po, pe, m)
+            torch.cuda.synchronize()
+            plan.close()
+            seg.append((host(po)[:int(m.item()) + 1], host(pe)[:int(m.item())]))
+    else:
+        for g in range(G):
+            shares[g].dispatch(xs[g], e2g, dest_orders[g])
+        torch.cuda.synchronize()
+        seg = [(host(sh.seg_offset), host(sh.seg_expert)) for sh in shares]
     rets = [torch.zeros_like(sh.send_buf) for sh in shares]
     for dst in range(G):
         local = [e for e in range(E) if e2g[e] == dst]

@@ -18,8 +18,8 @@ def H():
     return harness
 
 
-def check_cluster(H, cfg, n_shared=0):
-    res = H.run_emulated_cluster(cfg, n_shared=n_shared)
+def check_cluster(H, cfg, n_shared=0, chunked=False):
+    res = H.run_emulated_cluster(cfg, n_shared=n_shared, chunked=chunked)
     inp0 = res["inputs"][0]
     worst = 0.0
     for g in range(cfg.G):
@@ -49,6 +49,17 @@ def test_c1_tiny_full_layer(H):
 def test_reduced_configs_full_layer(H, name, kw, n_shared):
     cfg = W.scaled(W.get_config(name), **kw)
     check_cluster(H, cfg, n_shared)
+
+
+@pytest.mark.parametrize("name,kw", [
+    ("c1_tiny_fp32", dict()),
+    ("c2_mixtral", dict(T=96, H=256, F=384, G=4)),
+    ("c3_switch", dict(T=200, H=128, F=256, E=16, G=4)),               # capacity drops on every GPU
+])
+def test_full_layer_with_the_preemptive_send_plan(H, name, kw):
+    """Same layer, send buffers laid out chunk by chunk for the rounds of the library's schedule."""
+    cfg = W.scaled(W.get_config(name), **kw) if kw else W.get_config(name)
+    check_cluster(H, cfg, chunked=True)
 
 
 def test_two_colocated_models_concurrent_streams_match_serial(H):

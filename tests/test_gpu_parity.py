@@ -179,6 +179,56 @@ def test_dispatch_alone_and_after_in_place_index_rewrite(H, cfg):
     check(idx_a)
 
 
+CHUNK_CASES = [small("c2_mixtral", T=300, H=264), small("c3_switch", T=700, H=128), small("c5_finegrained", T=260, H=64),
+               small("c1_tiny_fp32", T=37, H=100, E=5, k=3, G=5), small("c5_finegrained", T=3000, H=64, E=160, k=9, G=16)]
+
+
+@pytest.mark.parametrize("cfg", CHUNK_CASES, ids=lambda c: "%s-T%d-E%d-k%d-G%d" % (c.name, c.T, c.E, c.k, c.G))
+def test_dispatch_chunks(H, cfg):
+    """Send buffer in the layout of a preemptive plan: bit-exact against the oracle for plans that
+    cover too little, too much, nothing, name no GPU, and for the plan of the Appendix A rounds."""
+    P = H.P
+    inp = W.make_layer_inputs(cfg)
+    idx_ref, _, _ = O.route(inp["x"], inp["w_gate"], inp["gate_bias"], cfg.k, cfg.renorm)
+    e2g = inp["expert_to_gpu"]
+    _, dc, _, _ = O.traffic(idx_ref, e2g, cfg.G, cfg.capacity)
+    r = np.random.default_rng(cfg.seed_base + 9)
+    plans = [[], [(g, 10 ** 9) for g in r.permutation(cfg.G)]]
+    plans.append([(int(r.integers(-1, cfg.G + 1)), int(r.integers(-2, max(2, 2 * dc.max() // 3)))) for _ in range(40)])
+    plans.append([(int(r.integers(0, cfg.G)), int(r.integers(0, 9))) for _ in range(4096)])     # the largest plan allowed
+    # the traffic matrix of the workload with this GPU's measured row, planned by the library
+    g = 0
+    D = np.array(W.make_traffic_matrix(cfg)["D"], dtype=np.int64)
+    D[g] = dc
+    plans.append(P.aurora_chunks(D, None, g))
+    sh = H.Share(cfg)
+    x = H.dev(inp["x"], cfg.dtype)
+    sh.idx.copy_(torch.from_numpy(idx_ref))
+    for chunks in plans:
+        ref = O.dispatch_chunks(inp["x"], idx_ref, e2g, chunks, cfg.capacity)
+        nc = len(chunks) + cfg.G
+        plan = P.MoeChunkPlan(sh.ctx, e2g, chunks)
+        co = torch.full((nc + 1,), -7, dtype=torch.int32, device=H.DEV)
+        po = torch.full((nc + cfg.E + 1,), -7, dtype=torch.int32, device=H.DEV)
+        pe = torch.full((nc + cfg.E,), -7, dtype=torch.int32, device=H.DEV)
+        npieces = torch.zeros(1, dtype=torch.int32, device=H.DEV)
+        sh.send_buf.zero_()
+        sh.slot_to_row.fill_(-9)
+        sh.row_to_slot.fill_(-9)
+        P.moe_dispatch_chunks(sh.ctx, plan, x, sh.idx, sh.send_buf, sh.slot_to_row, sh.row_to_slot, co, po, pe, npieces)
+        torch.cuda.synchronize()
+        n = ref["n_rows"]
+        assert np.array_equal(H.host(sh.slot_to_row), ref["slot_to_row"])
+        assert np.array_equal(H.host(sh.row_to_slot)[:n], ref["row_to_slot"])
+        assert np.array_equal(H.host(sh.send_buf)[:n], ref["send_buf"])                     # bitwise row copies
+        assert np.array_equal(H.host(co), ref["chunk_offset"])
+        m = int(npieces.item())
+        assert m == len(ref["piece_expert"])
+        assert np.array_equal(H.host(po)[:m + 1], ref["piece_offset"])
+        assert np.array_equal(H.host(pe)[:m], ref["piece_expert"])
+        plan.close()
+
+
 def make_segments(r, R, nseg, n_local):
     cuts = np.sort(r.integers(0, R + 1, size=nseg - 1))
     off = [0] + [int(c) for c in cuts] + [R]

@@ -145,3 +145,53 @@ def test_colocate_case1_and_config4_shapes():
     pair, bott = P.colocate_match(Da, Db16)
     assert bott == OM.best_pairing_threshold(Da, Db16)[0]
     assert len(set(pair)) == 8
+
+
+@pytest.mark.parametrize("hetero", [False, True])
+def test_aurora_chunks_follow_the_library_rounds(hetero):
+    """The decomposition into rounds is not unique, so chunk lists are checked against the rounds
+    the library itself returned, with the properties the oracle's chunk lists are pinned to."""
+    r = np.random.default_rng(77)
+    for n in (2, 3, 5, 8, 16):
+        for _ in range(3):
+            D = random_D(r, n, hi=200)
+            B = list(r.choice([1.0, 0.8, 0.5, 0.4], size=n)) if hetero else None
+            plan = P.aurora_order(D, B)
+            receivers = [dict() for _ in range(plan["n_rounds"])]
+            for g in range(n):
+                chunks = P.aurora_chunks(D, B, g)
+                got = np.zeros(n, dtype=np.int64)
+                cap = np.zeros(n)                                                  # tokens the rounds so far could carry to each destination
+                rr = 0
+                for dest, rows in chunks:
+                    assert rows > 0 and dest != g
+                    rate = 1.0 if B is None else min(B[g], B[dest])
+                    got[dest] += rows
+                    # the chunk belongs to the round at whose end the whole tokens sent so far reach its cumulative count
+                    while True:
+                        assert rr < plan["n_rounds"]
+                        j = plan["dst"][rr][g]
+                        if j >= 0:
+                            cap[j] = min(cap[j] + plan["duration"][rr] * rate if j == dest else cap[j] + plan["duration"][rr] * min(1.0 if B is None else B[g], 1.0 if B is None else B[j]), D[g][j])
+                        rr += 1
+                        if j == dest and np.floor(cap[dest] + 1e-6) >= got[dest]:
+                            break
+                    assert np.floor(cap[dest] + 1e-6) == got[dest]                 # whole tokens of the cumulative amount, no more
+                    assert receivers[rr - 1].setdefault(dest, g) == g              # contention-free
+                want = np.array(D[g], dtype=np.int64)
+                want[g] = 0
+                assert np.array_equal(got, want)
+    # the same lists as the oracle when the decomposition is forced: a permutation matrix has one round
+    D = np.zeros((4, 4), dtype=np.int64)
+    for i, j in enumerate([2, 3, 1, 0]):
+        D[i, j] = 50 + i
+    for g in range(4):
+        assert P.aurora_chunks(D, None, g) == OS.chunks_from_rounds(D.tolist(), None, g)[0]
+
+
+def test_aurora_chunks_argument_errors():
+    D = np.array([[0, 3], [4, 0]], dtype=np.int64)
+    with pytest.raises(P.MoeError):
+        P.aurora_chunks(D, None, 2)
+    with pytest.raises(P.MoeError):
+        P.aurora_chunks(D, [1.0, -1.0], 0)
