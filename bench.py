@@ -154,7 +154,42 @@ def build_workload(cfg, torch, P, W):
                 idx=idx, w=w, expert_count=expert_count, dest_count=dest_count, n_dropped=n_dropped,
                 send_buf=send_buf, slot_to_row=s2r, row_to_slot=r2s, seg_offset=seg_offset, seg_expert=seg_expert,
                 recv=recv, ffn_out=ffn_out, ret=ret, ffn_off=off, ffn_exp=exp, local=local, dest_order=dest_order,
-                self_spans=self_spans, n_chunks=len(chunks), keep=(ctx, x, wg, bias, experts, table, ws, chunk_plan))
+                self_spans=self_spans, n_chunks=len(chunks), D=D, rates=rates, plan=plan, keep=(ctx, x, wg, bias, experts, table, ws, chunk_plan))
+
+
+PAPER_LINK_GBPS = 12.5        # the 100 Gbps port of the paper's simulation set-up (Sec. 8.1), in GB/s
+
+
+def paper_model(cfg, wl, stage_ms, P):
+    """The paper's own metrics for this synthetic traffic matrix (Sec. 4.1 Eqn. 3, Sec. 8.1), with the
+    computation times measured here and the all-to-alls modelled on the big switch of Sec. 2.4:
+    inference time = |G| + max|N_i| + max|F_i| + max|C_i| + |A| where G = route + traffic + dispatch,
+    F = expert FFN, A = combine on the GPU under test (the one that receives most), and the
+    communication time of a transmission order is its completion time on ports of PAPER_LINK_GBPS
+    (token rows of H elements).  Orders: the library's (Algorithm 1), the bound of Theorem 2 / 4 that the
+    rounds of Appendix A attain, shortest flow first, and a seeded random order."""
+    D, rates, plan = wl["D"], wl["rates"], wl["plan"]
+    G_ = cfg.G
+    row_bytes = cfg.H * (2 if cfg.dtype == "bf16" else 4)
+    ms_per_unit = row_bytes / (PAPER_LINK_GBPS * 1e9) * 1e3          # one token over a rate-1 port
+    off = D.astype(np.float64).copy()
+    np.fill_diagonal(off, 0.0)
+    sjf = np.array([sorted(range(G_), key=lambda j: (off[i, j], j)) for i in range(G_)], dtype=np.int32)
+    rng = np.random.default_rng(cfg.seed_base + 77)
+    rcs = np.array([rng.permutation(G_) for _ in range(G_)], dtype=np.int32)
+    comm = {"theorem_bound": plan["bmax"] * ms_per_unit,
+            "aurora_order": P.aurora_simulate(D, rates, plan["dest_order"]) * ms_per_unit,
+            "shortest_first": P.aurora_simulate(D, rates, sjf) * ms_per_unit,
+            "random_order": P.aurora_simulate(D, rates, rcs) * ms_per_unit}
+    g_ms = stage_ms["route"] + stage_ms["traffic"] + stage_ms["dispatch"]
+    f_ms, a_ms = stage_ms["expert_ffn"], stage_ms["combine"]
+    out = {"link_GBps": PAPER_LINK_GBPS, "comm_ms_one_all_to_all": {k: round(v, 4) for k, v in comm.items()}}
+    for k, c in comm.items():
+        # the second all-to-all is the first reversed: same duration (Sec. 2.2)
+        t = P.aurora_layer_time([g_ms], [c], [f_ms], [c], [a_ms])
+        out["inference_ms_" + k] = round(t, 4)
+        out["gpu_utilisation_" + k] = round((g_ms + f_ms + a_ms) / t, 4)
+    return out
 
 
 def capture(torch, fn, reps=1):
@@ -307,6 +342,7 @@ def main():
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": GEMM1_TRAFFIC_BYTES.get(cfg.name),
                      "launch_ms": float(gemm_ms[1]), "flops_per_launch": flops_gemm1},
     }
+    line["paper_model"] = paper_model(cfg, wl, stage_ms, P)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, wl, W)
     print(json.dumps(line))

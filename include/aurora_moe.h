@@ -257,6 +257,46 @@ int aurora_simulate(int32_t n, const int64_t* D, const double* B, const int32_t*
 int colocate_match(int32_t na, int32_t nb, const int64_t* Da, const int64_t* Db, int32_t* pair,
                    double* bottleneck);
 
+/* GPU assignment on a heterogeneous cluster (Sec. 5.1, Theorem 3): experts sorted
+ * by the tokens they process, descending, meet GPUs sorted by performance,
+ * descending; ties keep the lower index first.  One expert per GPU.
+ *   load HOST [n] >= 0, perf HOST [n] > 0, expert_to_gpu HOST [n] out; n <= 256 */
+int aurora_assign(int32_t n, const int64_t* load, const double* perf, int32_t* expert_to_gpu);
+
+/* Bottleneck assignment (the matching of Sec. 6.2 Case II on an arbitrary table):
+ * one item per GPU, minimising the largest W[g*n + item]; binary search over the
+ * sorted weights with Hopcroft-Karp as the feasibility test.
+ *   W HOST [n*n] finite, item_of_gpu HOST [n] out, bottleneck HOST [1] out; n <= 256 */
+int aurora_bottleneck_assign(int32_t n, const double* W, int32_t* item_of_gpu, double* bottleneck);
+
+/* Colocation on a heterogeneous cluster by the decoupled method of Sec. 7.2: first
+ * colocate_match on the traffic alone, then GPUs against the pairs found, the edge
+ * weight being the inference time of the pair on that GPU.  The paper prints no
+ * formula for that time, so it is an input:
+ *   time3 HOST [n*n*n] finite: time3[(g*n + i)*n + j] = GPU g hosting expert i of a and j of b
+ *   pair HOST [n] out (expert of b with expert i of a), gpu_of_pair HOST [n] out,
+ *   value HOST [1] out = the largest time3 used; n <= 64 */
+int colocate_hetero_match(int32_t n, const int64_t* Da, const int64_t* Db, const double* time3, int32_t* pair,
+                          int32_t* gpu_of_pair, double* value);
+
+/* Eqn. 1 (Sec. 4.1): max_i(G_i + N_i) + max_j(F_j + C_j) + max_k A_k over the n GPUs.
+ *   G, N, F, C, A HOST [n] durations; t_out HOST [1] */
+int aurora_layer_time(int32_t n, const double* G, const double* N, const double* F, const double* C,
+                      const double* A, double* t_out);
+
+/* End times of the components of two colocated models (Sec. 6.1, Table 2) and the
+ * inference time t = E_{A^b} + |G^a| (Eqn. 4).  Na, Nb: stand-alone durations of the
+ * first all-to-alls, NaNb: their aggregated duration; the second all-to-alls are the
+ * first ones reversed and take the same durations.  A communication component ends at
+ * the later of the table's aggregated duration and its earliest start plus its own
+ * duration (read as absolute times the table's entries could end before the component
+ * may start).  All inputs finite and >= 0. */
+typedef struct {
+    double Gb, Na, Fa, Nb, Fb, Ca, Aa, Cb, Ab, Ga, t;
+} aurora_coloc_times;
+int aurora_colocated_time(double Ga, double Gb, double Fa, double Fb, double Aa, double Ab, double Na, double Nb,
+                          double NaNb, aurora_coloc_times* out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,12 @@ class aurora_schedule(C.Structure):
                 ("makespan_rounds", C.c_double), ("makespan_order", C.c_double)]
 
 
+class aurora_coloc_times(C.Structure):
+    _fields_ = [(k, C.c_double) for k in ("Gb", "Na", "Fa", "Nb", "Fb", "Ca", "Aa", "Cb", "Ab", "Ga", "t")]
+
+
 _vp, _i32, _sz = C.c_void_p, C.c_int32, C.c_size_t
+_pd, _pi64, _pi32 = C.POINTER(C.c_double), C.POINTER(C.c_int64), C.POINTER(C.c_int32)
 SIGNATURES = {
     "moe_status_str": (C.c_char_p, [C.c_int]),
     "moe_last_error": (C.c_char_p, []),
@@ -48,6 +53,11 @@ SIGNATURES = {
                                 C.POINTER(_i32), C.POINTER(_i32), C.POINTER(_i32)]),
     "aurora_simulate": (C.c_int, [_i32, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(_i32),
                                   C.POINTER(C.c_double)]),
+    "aurora_assign": (C.c_int, [_i32, _pi64, _pd, _pi32]),
+    "aurora_bottleneck_assign": (C.c_int, [_i32, _pd, _pi32, _pd]),
+    "colocate_hetero_match": (C.c_int, [_i32, _pi64, _pi64, _pd, _pi32, _pi32, _pd]),
+    "aurora_layer_time": (C.c_int, [_i32, _pd, _pd, _pd, _pd, _pd, _pd]),
+    "aurora_colocated_time": (C.c_int, [C.c_double] * 9 + [C.POINTER(aurora_coloc_times)]),
     "colocate_match": (C.c_int, [_i32, _i32, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(_i32),
                                  C.POINTER(C.c_double)]),
 }

@@ -302,3 +302,56 @@ def colocate_match(Da, Db):
     bott = C.c_double()
     _check("colocate_match", lib.colocate_match(A.shape[0], Bm.shape[0], Ap, Bp, pair, C.byref(bott)))
     return list(pair), bott.value
+
+
+def aurora_assign(load, perf):
+    """Theorem 3: expert_to_gpu for one expert per GPU."""
+    lib = _lib.load()
+    L = np.ascontiguousarray(load, dtype=np.int64)
+    Pf = np.ascontiguousarray(perf, dtype=np.float64)
+    out = (C.c_int32 * len(L))()
+    _check("aurora_assign", lib.aurora_assign(len(L), L.ctypes.data_as(C.POINTER(C.c_int64)),
+                                              Pf.ctypes.data_as(C.POINTER(C.c_double)), out))
+    return list(out)
+
+
+def aurora_bottleneck_assign(W):
+    lib = _lib.load()
+    Wm = np.ascontiguousarray(W, dtype=np.float64)
+    n = Wm.shape[0]
+    item = (C.c_int32 * n)()
+    v = C.c_double()
+    _check("aurora_bottleneck_assign", lib.aurora_bottleneck_assign(n, Wm.ctypes.data_as(C.POINTER(C.c_double)), item,
+                                                                    C.byref(v)))
+    return list(item), v.value
+
+
+def colocate_hetero_match(Da, Db, time3):
+    """Two-stage matching of Sec. 7.2; returns (pair, gpu_of_pair, value)."""
+    lib = _lib.load()
+    A, Ap = _i64_matrix(Da)
+    Bm, Bp = _i64_matrix(Db)
+    T3 = np.ascontiguousarray(time3, dtype=np.float64)
+    n = A.shape[0]
+    pair, gpu = (C.c_int32 * n)(), (C.c_int32 * n)()
+    v = C.c_double()
+    _check("colocate_hetero_match", lib.colocate_hetero_match(n, Ap, Bp, T3.ctypes.data_as(C.POINTER(C.c_double)), pair,
+                                                              gpu, C.byref(v)))
+    return list(pair), list(gpu), v.value
+
+
+def aurora_layer_time(G, N, F, Cc, A):
+    lib = _lib.load()
+    arrs = [np.ascontiguousarray(a, dtype=np.float64) for a in (G, N, F, Cc, A)]
+    t = C.c_double()
+    _check("aurora_layer_time", lib.aurora_layer_time(len(arrs[0]), *[a.ctypes.data_as(C.POINTER(C.c_double)) for a in arrs],
+                                                      C.byref(t)))
+    return t.value
+
+
+def aurora_colocated_time(Ga, Gb, Fa, Fb, Aa, Ab, Na, Nb, NaNb):
+    """Table 2 / Eqn. 4; returns a dict of end times with 't' the inference time."""
+    lib = _lib.load()
+    out = _lib.aurora_coloc_times()
+    _check("aurora_colocated_time", lib.aurora_colocated_time(Ga, Gb, Fa, Fb, Aa, Ab, Na, Nb, NaNb, C.byref(out)))
+    return {k: getattr(out, k) for k, _ in out._fields_}

@@ -474,3 +474,128 @@ extern "C" int colocate_match(int32_t na, int32_t nb, const int64_t* Da, const i
     }
     return MOE_OK;
 }
+
+// ---------------------------------------------------------------------------------------------
+// Theorem 3 (Sec. 5.1): the expert with the r-th largest load on the GPU with the r-th highest
+// performance; ties keep the lower index first on both sides.
+extern "C" int aurora_assign(int32_t n, const int64_t* load, const double* perf, int32_t* expert_to_gpu) {
+    if (!load || !perf || !expert_to_gpu) return moe_set_error(MOE_EINVAL, "aurora_assign: NULL argument");
+    if (n < 1 || n > MOE_MAX_E) return moe_set_error(MOE_ESHAPE, "aurora_assign: need 1 <= n <= %d", MOE_MAX_E);
+    for (int i = 0; i < n; ++i) {
+        if (load[i] < 0) return moe_set_error(MOE_EINVAL, "aurora_assign: negative load");
+        if (!(perf[i] > 0.0) || !std::isfinite(perf[i])) return moe_set_error(MOE_EINVAL, "aurora_assign: performance must be finite and > 0");
+    }
+    try {
+        std::vector<int> experts(n), gpus(n);
+        for (int i = 0; i < n; ++i) experts[i] = gpus[i] = i;
+        std::stable_sort(experts.begin(), experts.end(), [&](int a, int b) { return load[a] > load[b]; });
+        std::stable_sort(gpus.begin(), gpus.end(), [&](int a, int b) { return perf[a] > perf[b]; });
+        for (int r = 0; r < n; ++r) expert_to_gpu[experts[r]] = gpus[r];
+    } catch (const std::bad_alloc&) {
+        return moe_set_error(MOE_ENOMEM, "aurora_assign: host allocation failed");
+    }
+    return MOE_OK;
+}
+
+namespace {
+
+// Perfect matching rows -> columns of an n x n weight table that minimises the largest weight used:
+// binary search over the sorted distinct weights (as ranks), Hopcroft-Karp as the feasibility test.
+int bottleneck_perfect(int n, const double* W, int32_t* col_of_row, double* value) {
+    std::vector<double> vals(W, W + (size_t)n * n);
+    std::sort(vals.begin(), vals.end());
+    vals.erase(std::unique(vals.begin(), vals.end()), vals.end());
+    std::vector<int64_t> rank((size_t)n * n);
+    for (size_t i = 0; i < rank.size(); ++i) rank[i] = std::lower_bound(vals.begin(), vals.end(), W[i]) - vals.begin();
+    size_t lo = 0, hi = vals.size() - 1;             // every edge allowed: a perfect matching exists
+    while (lo < hi) {
+        const size_t mid = (lo + hi) / 2;
+        HopcroftKarp hk(n, n, rank, (int64_t)mid);
+        if (hk.run() == n) hi = mid; else lo = mid + 1;
+    }
+    HopcroftKarp hk(n, n, rank, (int64_t)lo);
+    if (hk.run() != n) return moe_set_error(MOE_EINTERNAL, "bottleneck matching: no perfect matching at the largest weight");
+    for (int i = 0; i < n; ++i) col_of_row[i] = hk.ml[i];
+    *value = vals[lo];
+    return MOE_OK;
+}
+
+int check_weights(const char* who, size_t count, const double* W) {
+    for (size_t i = 0; i < count; ++i)
+        if (!std::isfinite(W[i])) return moe_set_error(MOE_EINVAL, "%s: weight %zu is not finite", who, i);
+    return MOE_OK;
+}
+
+}  // namespace
+
+extern "C" int aurora_bottleneck_assign(int32_t n, const double* W, int32_t* item_of_gpu, double* bottleneck) {
+    if (!W || !item_of_gpu || !bottleneck) return moe_set_error(MOE_EINVAL, "aurora_bottleneck_assign: NULL argument");
+    if (n < 1 || n > MOE_MAX_E) return moe_set_error(MOE_ESHAPE, "aurora_bottleneck_assign: need 1 <= n <= %d", MOE_MAX_E);
+    int rc = check_weights("aurora_bottleneck_assign", (size_t)n * n, W);
+    if (rc != MOE_OK) return rc;
+    try {
+        return bottleneck_perfect(n, W, item_of_gpu, bottleneck);
+    } catch (const std::bad_alloc&) {
+        return moe_set_error(MOE_ENOMEM, "aurora_bottleneck_assign: host allocation failed");
+    }
+}
+
+extern "C" int colocate_hetero_match(int32_t n, const int64_t* Da, const int64_t* Db, const double* time3, int32_t* pair,
+                                     int32_t* gpu_of_pair, double* value) {
+    if (!Da || !Db || !time3 || !pair || !gpu_of_pair || !value)
+        return moe_set_error(MOE_EINVAL, "colocate_hetero_match: NULL argument");
+    if (n < 1 || n > MOE_MAX_G) return moe_set_error(MOE_ESHAPE, "colocate_hetero_match: need 1 <= n <= %d", MOE_MAX_G);
+    int rc = check_weights("colocate_hetero_match", (size_t)n * n * n, time3);
+    if (rc != MOE_OK) return rc;
+    double traffic_bottleneck = 0.0;
+    rc = colocate_match(n, n, Da, Db, pair, &traffic_bottleneck);       // stage one: experts against experts, traffic only
+    if (rc != MOE_OK) return rc;
+    try {
+        std::vector<double> W((size_t)n * n);                           // stage two: GPUs against the pairs found
+        for (int g = 0; g < n; ++g)
+            for (int i = 0; i < n; ++i) W[(size_t)g * n + i] = time3[((size_t)g * n + i) * n + pair[i]];
+        std::vector<int32_t> item(n);
+        rc = bottleneck_perfect(n, W.data(), item.data(), value);
+        if (rc != MOE_OK) return rc;
+        for (int g = 0; g < n; ++g) gpu_of_pair[item[g]] = g;
+    } catch (const std::bad_alloc&) {
+        return moe_set_error(MOE_ENOMEM, "colocate_hetero_match: host allocation failed");
+    }
+    return MOE_OK;
+}
+
+extern "C" int aurora_layer_time(int32_t n, const double* G, const double* N, const double* F, const double* C,
+                                 const double* A, double* t_out) {
+    if (!G || !N || !F || !C || !A || !t_out) return moe_set_error(MOE_EINVAL, "aurora_layer_time: NULL argument");
+    if (n < 1) return moe_set_error(MOE_ESHAPE, "aurora_layer_time: need n >= 1");
+    double gn = G[0] + N[0], fc = F[0] + C[0], a = A[0];
+    for (int i = 1; i < n; ++i) {
+        gn = std::max(gn, G[i] + N[i]);
+        fc = std::max(fc, F[i] + C[i]);
+        a = std::max(a, A[i]);
+    }
+    *t_out = gn + fc + a;
+    return MOE_OK;
+}
+
+extern "C" int aurora_colocated_time(double Ga, double Gb, double Fa, double Fb, double Aa, double Ab, double Na, double Nb,
+                                     double NaNb, aurora_coloc_times* out) {
+    if (!out) return moe_set_error(MOE_EINVAL, "aurora_colocated_time: NULL argument");
+    const double in[9] = {Ga, Gb, Fa, Fb, Aa, Ab, Na, Nb, NaNb};
+    for (double v : in)
+        if (!(v >= 0.0) || !std::isfinite(v)) return moe_set_error(MOE_EINVAL, "aurora_colocated_time: durations must be finite and >= 0");
+    // the second all-to-all is the first one reversed: same stand-alone and aggregated durations
+    const double Ca = Na, Cb = Nb, CaCb = NaNb;
+    out->Gb = Gb;
+    out->Na = Na;
+    out->Fa = std::max(Gb, Na) + Fa;
+    out->Nb = std::max(NaNb, Gb + Nb);
+    out->Fb = std::max(out->Fa, out->Nb) + Fb;
+    out->Ca = std::max(NaNb + Ca, out->Fa + Ca);
+    out->Aa = std::max(out->Fb, out->Ca) + Aa;
+    out->Cb = std::max(NaNb + CaCb, out->Fb + Cb);
+    out->Ab = std::max(out->Aa, out->Cb) + Ab;
+    out->Ga = out->Ab + Ga;
+    out->t = out->Ga;
+    return MOE_OK;
+}

@@ -8,6 +8,7 @@ import pytest
 import paper_2410_17043_amd as P
 import workloads as W
 from oracle import matching as OM
+from oracle import planning as OP
 from oracle import schedule as OS
 
 
@@ -195,3 +196,64 @@ def test_aurora_chunks_argument_errors():
         P.aurora_chunks(D, None, 2)
     with pytest.raises(P.MoeError):
         P.aurora_chunks(D, [1.0, -1.0], 0)
+
+
+def test_aurora_assign_is_theorem3():
+    r = np.random.default_rng(80)
+    for n in (1, 2, 5, 8, 64, 256):
+        for _ in range(4):
+            load = r.integers(0, 50, size=n)                      # many ties
+            perf = r.choice([1.0, 0.8, 0.5, 0.4], size=n)
+            assert P.aurora_assign(load, perf) == OP.thm3_assign(load.tolist(), perf.tolist())
+    with pytest.raises(P.MoeError):
+        P.aurora_assign([1, 2], [1.0, 0.0])
+    with pytest.raises(P.MoeError):
+        P.aurora_assign([1, -2], [1.0, 1.0])
+
+
+def test_bottleneck_assign_and_hetero_colocation_against_the_oracle():
+    r = np.random.default_rng(81)
+    for n in (1, 2, 3, 5, 6):
+        for _ in range(6):
+            Wt = r.integers(0, 25, size=(n, n)).astype(float)
+            item, v = P.aurora_bottleneck_assign(Wt)
+            assert sorted(item) == list(range(n))
+            assert v == OP.bottleneck_assign_brute(Wt.tolist())[0] == max(Wt[g][item[g]] for g in range(n))
+    for n in (2, 3, 4):
+        for _ in range(5):
+            Da, Db = random_D(r, n), random_D(r, n)
+            perf = r.choice([1.0, 0.8, 0.5, 0.4], size=n)
+            Wp = np.array(OM.pair_weights(Da.tolist(), Db.tolist()), dtype=float)
+            fa, fb = Da.sum(0) - np.diag(Da), Db.sum(0) - np.diag(Db)
+            time3 = ((fa[None, :, None] + fb[None, None, :]) + 2.0 * Wp[None]) / perf[:, None, None]
+            pair, gpu, v = P.colocate_hetero_match(Da, Db, time3)
+            assert sorted(pair) == list(range(n)) and sorted(gpu) == list(range(n))
+            assert v == max(time3[gpu[i]][i][pair[i]] for i in range(n))
+            # stage one attains the traffic bottleneck; stage two is optimal for the pairs it was given
+            assert max(Wp[i][pair[i]] for i in range(n)) == OM.best_pairing_brute(Da.tolist(), Db.tolist())[0]
+            W2 = [[time3[g][i][pair[i]] for i in range(n)] for g in range(n)]
+            assert v == OP.bottleneck_assign_brute(W2)[0]
+            assert v >= OP.optimum_3d(time3.tolist()) - 1e-12
+    # a large instance finishes and is a valid matching
+    n = 64
+    Da, Db = random_D(r, n), random_D(r, n)
+    time3 = r.random((n, n, n))
+    pair, gpu, v = P.colocate_hetero_match(Da, Db, time3)
+    assert sorted(pair) == list(range(n)) and sorted(gpu) == list(range(n))
+    assert v == max(time3[gpu[i]][i][pair[i]] for i in range(n))
+
+
+def test_time_model_against_the_oracle():
+    r = np.random.default_rng(82)
+    for _ in range(50):
+        n = int(r.integers(1, 17))
+        G, N, F, Cc, A = (r.random(n) * 10 for _ in range(5))
+        assert P.aurora_layer_time(G, N, F, Cc, A) == pytest.approx(
+            OP.layer_time(G.tolist(), N.tolist(), F.tolist(), Cc.tolist(), A.tolist()), rel=1e-15)
+        v = [float(x) for x in r.integers(0, 20, size=9)]
+        got = P.aurora_colocated_time(*v)
+        ref = OP.colocated_time(*v)
+        assert all(got[k] == ref[k] for k in got)
+    assert P.aurora_colocated_time(1, 1, 10, 10, 1, 1, 1, 1, 2)["t"] == 24      # the compute-bound example worked by hand
+    with pytest.raises(P.MoeError):
+        P.aurora_colocated_time(1, 1, 1, 1, 1, 1, 1, 1, -1)
