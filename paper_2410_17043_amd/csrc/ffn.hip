@@ -556,13 +556,24 @@ __global__ __launch_bounds__(256) void gemm_bf16_tail_kernel(TileMap m, int N, i
     const int tid = threadIdx.x;
     const f32x4* src = reinterpret_cast<const f32x4*>(reinterpret_cast<const char*>(partial) +
                                                       (size_t)tt * plan.parts * kPartialBytes) + (size_t)i * 16 * 256 + tid;
+    // all pieces of four accumulator quads are requested before the first is added (plan_tail makes at most
+    // 8 pieces): the pass is a latency-bound stream otherwise
     f32x4 sum[16];
 #pragma unroll
-    for (int q = 0; q < 16; ++q) sum[q] = src[q * 256];
-    for (int p = 1; p < plan.parts; ++p) {
-        const f32x4* sp = src + (size_t)p * (kPartialBytes / 16);
+    for (int q0 = 0; q0 < 16; q0 += 4) {
+        f32x4 v[8][4];
 #pragma unroll
-        for (int q = 0; q < 16; ++q) sum[q] += sp[q * 256];
+        for (int p = 0; p < 8; ++p)
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                v[p][u] = (p < plan.parts) ? src[(size_t)p * (kPartialBytes / 16) + (q0 + u) * 256] : f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            sum[q0 + u] = v[0][u];
+#pragma unroll
+            for (int p = 1; p < 8; ++p)
+                if (p < plan.parts) sum[q0 + u] += v[p][u];
+        }
     }
     f32x16 acc_i[4];
 #pragma unroll
