@@ -108,21 +108,36 @@ template <int EPI> __device__ __forceinline__ float epilogue(float a, float b) {
     return a;
 }
 
-// Remap tile number `id` of `total` = tiles_m * tiles_n so that (1) the blocks resident on one XCD
-// (ids equal mod 8) get consecutive virtual ids and (2) consecutive virtual ids walk GROUP_M
-// M-tiles before moving to the next N-tile, so an XCD's L2 holds few distinct tiles.  A
-// bijection on [0, total) for every total.
+// Tile number `id` of `total` = tiles_m * tiles_n -> (tile_m, tile_n); a bijection for every shape.
+// Blocks are handed to the 8 XCDs round-robin (XCD = id % 8), each XCD has its own L2, and all of them
+// share the memory-side cache.  The map gives XCD x a band of tiles_m / 8 consecutive M-tiles and lets it
+// walk ALL N-tiles for that band, in groups of at most 8 M-tiles, M fastest: the blocks resident on an XCD
+// form a patch of a few M-tiles by a few N-tiles (few distinct operand tiles in its L2), and the 8 XCDs
+// sweep the N-tiles in step with each other, so a B tile fetched for one XCD is in the memory-side cache
+// when the other seven ask for it and the A bands stay there for the whole sweep.  The tiles_m % 8
+// M-tiles that do not fill a band come last, cut evenly over the XCDs.
 __device__ __forceinline__ void tile_of_block(int id, int total, int tiles_m, int tiles_n, int* tm, int* tn) {
-    constexpr int GROUP_M = 8;
-    const int x = id % 8;                                    // XCD x owns ids x, x + 8, ...
-    const int vid = x * (total / 8) + min(x, total % 8) + id / 8;
-    const int per_group = GROUP_M * tiles_n;
-    const int g = vid / per_group;
-    const int first_m = g * GROUP_M;
-    const int gsz = min(tiles_m - first_m, GROUP_M);
-    const int in_g = vid - g * per_group;
-    *tm = first_m + in_g % gsz;
-    *tn = in_g / gsz;
+    const int x = id % 8, j = id / 8;                        // XCD and position in that XCD's sequence
+    const int q = tiles_m / 8;                               // M-tiles per band
+    const int band = q * tiles_n;                            // tiles of a band
+    if (j < band) {
+        const int ngroups = (q + 7) / 8;                     // groups of near-equal height, at most 8
+        const int gs = q / ngroups, extra = q % ngroups;     // the first `extra` groups hold gs + 1 M-tiles
+        const int big = extra * (gs + 1) * tiles_n;          // tiles in those
+        int g, in_g, h;
+        if (j < big) { h = gs + 1; g = j / (h * tiles_n); in_g = j - g * h * tiles_n; }
+        else { h = gs; g = (j - big) / (h * tiles_n); in_g = (j - big) - g * h * tiles_n; g += extra; }
+        const int first = g * gs + min(g, extra);            // first M-tile of the group inside the band
+        *tm = q * x + first + in_g % h;
+        *tn = in_g / h;
+        return;
+    }
+    const int lm = tiles_m - 8 * q;                          // left-over M-tiles (lm >= 1 here)
+    const int left = lm * tiles_n;
+    const int v = x * (left / 8) + min(x, left % 8) + (j - band);
+    *tm = 8 * q + v % lm;
+    *tn = v / lm;
+    (void)total;
 }
 
 // Tail splitting.  The grid runs in rounds of `ncu` tiles (one block per CU); the tiles of a last,
