@@ -111,8 +111,8 @@ template <int EPI> __device__ __forceinline__ float epilogue(float a, float b) {
 // Tile number `id` of `total` = tiles_m * tiles_n -> (tile_m, tile_n); a bijection for every shape.
 // Blocks are handed to the 8 XCDs round-robin (XCD = id % 8), each XCD has its own L2, and all of them
 // share the memory-side cache.  The map gives XCD x a band of tiles_m / 8 consecutive M-tiles and lets it
-// walk ALL N-tiles for that band, in groups of at most 8 M-tiles, M fastest: the blocks resident on an XCD
-// form a patch of a few M-tiles by a few N-tiles (few distinct operand tiles in its L2), and the 8 XCDs
+// walk ALL N-tiles for that band, in groups of 8 (then 4, 2, 1) M-tiles, M fastest: the blocks resident on an
+// XCD form a patch of a few M-tiles by a few N-tiles (few distinct operand tiles in its L2), and the 8 XCDs
 // sweep the N-tiles in step with each other, so a B tile fetched for one XCD is in the memory-side cache
 // when the other seven ask for it and the A bands stay there for the whole sweep.  The tiles_m % 8
 // M-tiles that do not fill a band come last, cut evenly over the XCDs.
@@ -121,13 +121,15 @@ __device__ __forceinline__ void tile_of_block(int id, int total, int tiles_m, in
     const int q = tiles_m / 8;                               // M-tiles per band
     const int band = q * tiles_n;                            // tiles of a band
     if (j < band) {
-        const int ngroups = (q + 7) / 8;                     // groups of near-equal height, at most 8
-        const int gs = q / ngroups, extra = q % ngroups;     // the first `extra` groups hold gs + 1 M-tiles
-        const int big = extra * (gs + 1) * tiles_n;          // tiles in those
-        int g, in_g, h;
-        if (j < big) { h = gs + 1; g = j / (h * tiles_n); in_g = j - g * h * tiles_n; }
-        else { h = gs; g = (j - big) / (h * tiles_n); in_g = (j - big) - g * h * tiles_n; g += extra; }
-        const int first = g * gs + min(g, extra);            // first M-tile of the group inside the band
+        // group heights: 8 as often as it fits, then the binary digits of the rest, so that a height always
+        // divides the 32 blocks resident on an XCD (a 8 x 4, 4 x 8, ... patch with no straddling rows)
+        int in_g = j, h = 8, first = 0, rest = q;
+        while (true) {
+            while (h > rest) h >>= 1;
+            const int sz = h * tiles_n;
+            if (in_g < sz) break;
+            in_g -= sz; first += h; rest -= h;
+        }
         *tm = q * x + first + in_g % h;
         *tn = in_g / h;
         return;
