@@ -17,8 +17,9 @@
 // pipelined by hand (see the kernel).  For SwiGLU the B tile holds 128 gate rows and 128 up
 // rows arranged so that a wave owns the gate and the up product of the same 64 columns: the
 // activation is applied on registers and the intermediate is written once, in bf16, as whole
-// 128-byte lines after a transpose through LDS.  Block ids are remapped so that the blocks
-// that share an XCD's L2 work on neighbouring tiles.
+// 128-byte lines after a transpose through LDS.  Tiles are numbered so that the blocks that
+// share an XCD's L2 form a compact patch and all XCDs sweep the N-tiles in step (see
+// tile_of_block); the tiles of a mostly empty last round are cut along K (see plan_tail).
 //
 // fp32 path (correctness configuration): plain 64x64x16 LDS-tiled vector-ALU GEMM.
 #include "common.h"
