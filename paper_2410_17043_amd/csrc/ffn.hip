@@ -145,7 +145,7 @@ __device__ __forceinline__ void tile_of_block(int id, int total, int tiles_m, in
 
 // Tail splitting.  The grid runs in rounds of `ncu` tiles (one block per CU); the tiles of a last,
 // mostly empty round would leave most CUs idle for a whole tile time.  When that round has at most
-// ncu / 4 tiles, each of them is cut along K into `parts` pieces that run as separate blocks
+// ncu / 2 tiles, each of them is cut along K into `parts` pieces that run as separate blocks
 // (1/parts of a tile time) and write fp32 partial tiles; a second small kernel adds the pieces
 // of a tile in piece order and applies the epilogue.  Everything here depends
 // only on the shapes, so results do not vary from run to run.
@@ -161,9 +161,10 @@ __device__ __forceinline__ TailPlan plan_tail(int total, int ncu, int nk) {
     const int rem = total % ncu;
     const int npairs = nk / 2;
     if (rem == 0) return p;
-    // 4 to 8 pieces of at least 16 k-tiles: fewer do not pay for the extra pass, more only add partial tiles
+    // up to 8 pieces of at least 16 k-tiles (more only add partial tiles); 2 or 3 pieces pay for the extra
+    // pass only when a piece is still long (64 k-tiles)
     const int parts = min(min(ncu / rem, npairs / 8), 8);
-    if (parts < 4) return p;
+    if (parts < 2 || (parts < 4 && npairs / parts < 32)) return p;
     p.pairs_per = (npairs + parts - 1) / parts;
     p.parts = (npairs + p.pairs_per - 1) / p.pairs_per;
     p.n_tail = rem;
@@ -639,7 +640,7 @@ int launch_bf16(const void* A, int lda, const TileMap& m, const ExpertTable& tab
                        reinterpret_cast<const uint16_t*>(A), lda, m, tab, which0, which1, N, K,
                        reinterpret_cast<uint16_t*>(C), ldc, tiles_n, ncu, partial);
     MOE_LAUNCH_CHECK("gemm_bf16_kernel");
-    hipLaunchKernelGGL((gemm_bf16_tail_kernel<EPI>), dim3(ncu), dim3(256), lds, st, m, N, K,   // ncu / 4 tiles at most, 4 blocks each
+    hipLaunchKernelGGL((gemm_bf16_tail_kernel<EPI>), dim3(2 * ncu), dim3(256), lds, st, m, N, K,   // ncu / 2 tiles at most, 4 blocks each
                        reinterpret_cast<uint16_t*>(C), ldc, tiles_n, ncu, partial);
     MOE_LAUNCH_CHECK("gemm_bf16_tail_kernel");
     return MOE_OK;

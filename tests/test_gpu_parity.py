@@ -250,6 +250,9 @@ FFN_CASES = [
     ("bf16", 2, 300, 2048, 2048, 1, 1),
     ("bf16", 1, 700, 2048, 2304, 3, 6),
     ("bf16", 0, 257, 3072, 2048, 2, 2),
+    # a last round that is between a quarter and half full: two and three pieces of 64 k-tiles
+    ("bf16", 2, 700, 4096, 4608, 1, 1),
+    ("bf16", 2, 500, 6144, 5120, 1, 1),
 ]
 
 
