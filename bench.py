@@ -157,6 +157,38 @@ def build_workload(cfg, torch, P, W):
                 self_spans=self_spans, n_chunks=len(chunks), D=D, rates=rates, plan=plan, keep=(ctx, x, wg, bias, experts, table, ws, chunk_plan))
 
 
+def box_reference(torch, wl, cfg):
+    """What this very box sustains, for orientation beside the published peaks: a plain device copy
+    (256 MiB read + 256 MiB written) and, for bf16 workloads, the vendor library's GEMM of the first FFN
+    GEMM's shape (one projection, no activation; torch.matmul -> hipBLASLt).  Neither is on the product path."""
+    dev = wl["recv"].device
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    ev[0].record()
+    for _ in range(5):
+        dst.copy_(src)
+    ev[1].record()
+    ev[1].synchronize()
+    out = {"copy_GBps": round(5 * 2 * (256 << 20) / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9, 1)}
+    del src, dst
+    if cfg.dtype == "bf16":
+        w1 = wl["keep"][4][0]["w1"]                              # [F, H] of the first local expert
+        recv = wl["recv"]
+        c = recv @ w1.t()
+        torch.cuda.synchronize()
+        ev[0].record()
+        for _ in range(5):
+            c = recv @ w1.t()
+        ev[1].record()
+        ev[1].synchronize()
+        flops = 5 * 2.0 * recv.shape[0] * w1.shape[0] * w1.shape[1]
+        out["vendor_gemm_bf16_TFLOPs"] = round(flops / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e12, 1)
+        out["vendor_gemm_shape"] = [int(recv.shape[0]), int(w1.shape[0]), int(w1.shape[1])]
+    return out
+
+
 PAPER_LINK_GBPS = 12.5        # the 100 Gbps port of the paper's simulation set-up (Sec. 8.1), in GB/s
 
 
@@ -343,6 +375,7 @@ def main():
                      "launch_ms": float(gemm_ms[1]), "flops_per_launch": flops_gemm1},
     }
     line["paper_model"] = paper_model(cfg, wl, stage_ms, P)
+    line["box_reference"] = box_reference(torch, wl, cfg)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, wl, W)
     print(json.dumps(line))
