@@ -266,9 +266,14 @@ __device__ __forceinline__ int tile_off(int row, int c) { return ((row >> 4) << 
 __device__ __forceinline__ float fast_silu(float a) {
     return a * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.44269504088896f * a));
 }
+// tanh-form GELU: 0.5 a (1 + tanh(u)) = a * sigmoid(2u), u = sqrt(2/pi) (a + 0.044715 a^3); one exp2 and one rcp
+__device__ __forceinline__ float fast_gelu(float a) {
+    const float u2 = 1.5957691216057308f * (a + 0.044715f * a * a * a);
+    return a * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.44269504088896f * u2));
+}
 template <int EPI> __device__ __forceinline__ float epilogue_bf16(float a, float b) {
     if (EPI == EPI_SILU) return fast_silu(a);
-    if (EPI == EPI_GELU) return gelu_tanh_f(a);
+    if (EPI == EPI_GELU) return fast_gelu(a);
     if (EPI == EPI_SWIGLU) return fast_silu(a) * b;
     return a;
 }
