@@ -23,6 +23,8 @@
 //
 // fp32 path (correctness configuration): plain 64x64x16 LDS-tiled vector-ALU GEMM.
 #include "common.h"
+#include <algorithm>
+#include <vector>
 
 namespace {
 
@@ -117,7 +119,7 @@ template <int EPI> __device__ __forceinline__ float epilogue(float a, float b) {
 // sweep the N-tiles in step with each other, so a B tile fetched for one XCD is in the memory-side cache
 // when the other seven ask for it and the A bands stay there for the whole sweep.  The tiles_m % 8
 // M-tiles that do not fill a band come last, cut evenly over the XCDs.
-__device__ __forceinline__ void tile_of_block(int id, int total, int tiles_m, int tiles_n, int* tm, int* tn) {
+__host__ __device__ __forceinline__ void tile_of_block(int id, int total, int tiles_m, int tiles_n, int* tm, int* tn) {
     const int x = id % 8, j = id / 8;                        // XCD and position in that XCD's sequence
     const int q = tiles_m / 8;                               // M-tiles per band
     const int band = q * tiles_n;                            // tiles of a band
@@ -155,7 +157,7 @@ struct TailPlan {
     int parts;         // pieces per tail tile (1: no tail)
     int pairs_per;     // k-tile pairs per piece
 };
-__device__ __forceinline__ TailPlan plan_tail(int total, int ncu, int nk) {
+__host__ __device__ __forceinline__ TailPlan plan_tail(int total, int ncu, int nk) {
     TailPlan p;
     p.n_full = total; p.n_tail = 0; p.parts = 1; p.pairs_per = nk / 2;
     const int rem = total % ncu;
@@ -664,6 +666,34 @@ int launch_f32(const void* A, int lda, const TileMap& m, const ExpertTable& tab,
 }
 
 }  // namespace
+
+// Host-side self check of the tile numbering and of the tail plan for a tiles_m x tiles_n grid with nk k-tiles
+// (not part of the published interface; used by the CPU tests): every tile is produced exactly once, whole
+// or as `parts` pieces that cover its k-tiles exactly once.
+extern "C" int moe_selfcheck_tile_order(int32_t tiles_m, int32_t tiles_n, int32_t ncu, int32_t nk) {
+    if (tiles_m < 1 || tiles_n < 1 || ncu < 1 || nk < 2 || (nk & 1)) return moe_set_error(MOE_EINVAL, "moe_selfcheck_tile_order: bad argument");
+    const int total = tiles_m * tiles_n;
+    std::vector<int> seen((size_t)total, 0);
+    for (int id = 0; id < total; ++id) {
+        int tm = -1, tn = -1;
+        tile_of_block(id, total, tiles_m, tiles_n, &tm, &tn);
+        if (tm < 0 || tm >= tiles_m || tn < 0 || tn >= tiles_n) return moe_set_error(MOE_EINTERNAL, "tile %d maps outside the grid", id);
+        if (seen[(size_t)tm * tiles_n + tn]++) return moe_set_error(MOE_EINTERNAL, "tile (%d, %d) is produced twice", tm, tn);
+    }
+    const TailPlan p = plan_tail(total, ncu, nk);
+    if (p.n_full + p.n_tail != total || p.n_full % ncu != 0 && p.n_tail != 0) return moe_set_error(MOE_EINTERNAL, "tail plan does not partition the tiles");
+    if (p.n_tail * p.parts > ncu && p.parts > 1) return moe_set_error(MOE_EINTERNAL, "more pieces than CUs");
+    if (p.parts > 1) {
+        int covered = 0;
+        for (int piece = 0; piece < p.parts; ++piece) {
+            const int lo = piece * p.pairs_per * 2, n = std::min(p.pairs_per * 2, nk - lo);
+            if (lo != covered || n < 2) return moe_set_error(MOE_EINTERNAL, "pieces do not tile the k range");
+            covered += n;
+        }
+        if (covered != nk) return moe_set_error(MOE_EINTERNAL, "pieces do not cover the k range");
+    }
+    return p.parts;
+}
 
 extern "C" size_t moe_ffn_workspace_bytes(int32_t R_max, int32_t H, int32_t F, int32_t act, int32_t dtype) {
     if (R_max < 0 || H <= 0 || F <= 0 || act < 0 || act > 2 || (dtype != MOE_F32 && dtype != MOE_BF16)) return 0;

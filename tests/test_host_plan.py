@@ -257,3 +257,28 @@ def test_time_model_against_the_oracle():
     assert P.aurora_colocated_time(1, 1, 10, 10, 1, 1, 1, 1, 2)["t"] == 24      # the compute-bound example worked by hand
     with pytest.raises(P.MoeError):
         P.aurora_colocated_time(1, 1, 1, 1, 1, 1, 1, 1, -1)
+
+
+def test_tile_order_and_tail_plan_cover_every_tile_once():
+    """The FFN's tile numbering (a bijection for every grid) and its K-split plan for a mostly empty
+    last round, run on the host by the library's own self check."""
+    import ctypes as C
+    from paper_2410_17043_amd import _lib
+    lib = _lib.load()
+    lib.moe_selfcheck_tile_order.restype = C.c_int
+    lib.moe_selfcheck_tile_order.argtypes = [C.c_int32] * 4
+    split = 0
+    for tiles_m in list(range(1, 70)) + [81, 89, 100, 255, 2393]:
+        for tiles_n in (1, 2, 3, 4, 7, 8, 11, 16, 22, 112):
+            for nk in (2, 32, 44, 64, 128, 448):
+                parts = lib.moe_selfcheck_tile_order(tiles_m, tiles_n, 256, nk)
+                assert parts >= 1, lib.moe_last_error()
+                rem = (tiles_m * tiles_n) % 256
+                if parts > 1:
+                    split += 1
+                    assert 0 < rem <= 128 and rem * parts <= 256 and nk // parts >= 16
+                    assert parts >= 4 or nk // parts >= 64
+    assert split > 100
+    assert lib.moe_selfcheck_tile_order(81, 112, 256, 128) == 2       # first GEMM of the Mixtral-shape share
+    assert lib.moe_selfcheck_tile_order(81, 16, 256, 448) == 8        # second GEMM
+    assert lib.moe_selfcheck_tile_order(0, 4, 256, 8) < 0
