@@ -5,8 +5,10 @@
  * Sec. 2.1 lists the phases: Gate -> first all-to-all (only its buffer side is
  * built: the send buffer, laid out in the transmission order planned by
  * Sec. 4.2) -> expert FFN -> second all-to-all (only its layout contract) ->
- * Aggregation; plus the two host-side planners of Sec. 4.2 / 5.2 (transmission
- * order) and Sec. 6.2 (expert colocation by bottleneck matching).
+ * Aggregation; plus the host-side planners of Sec. 4.2 / 5.2 (transmission
+ * order; Appendix A rounds as a chunk plan for the send buffer), Sec. 5.1 (GPU
+ * assignment), Sec. 6.2 and 7.2 (expert colocation by bottleneck matching) and
+ * the inference-time expressions of Sec. 4.1 and 6.1.
  *
  * Conventions
  *   - Every function returns MOE_OK (0) or a negative moe_status; nothing
