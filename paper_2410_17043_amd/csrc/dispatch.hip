@@ -441,7 +441,7 @@ __global__ __launch_bounds__(kLayoutThreads) void chunk_layout_kernel(ChunkTable
                 size[u] = hi - lo;
                 if (hi > lo)
                     for (int e = 0; e < E; ++e)               // experts of d whose slots meet [lo, hi)
-                        if (map.expert_gpu[e] == d && first[e] < hi && first[e] + kept[e] > lo) ++pieces[u];
+                        if (map.expert_gpu[e] == d && kept[e] > 0 && first[e] < hi && first[e] + kept[e] > lo) ++pieces[u];
             }
         }
         sum += size[u];
@@ -460,7 +460,7 @@ __global__ __launch_bounds__(kLayoutThreads) void chunk_layout_kernel(ChunkTable
                 const int d = tb.c_dest[c];
                 const int lo = min(tb.c_cumlo[c], dest_cnt[d]), hi = lo + size[u];
                 for (int e = 0; e < E; ++e)
-                    if (map.expert_gpu[e] == d && first[e] < hi && first[e] + kept[e] > lo) {
+                    if (map.expert_gpu[e] == d && kept[e] > 0 && first[e] < hi && first[e] + kept[e] > lo) {
                         piece_offset[piece0] = row0 + max(first[e], lo) - lo;
                         piece_expert[piece0] = e;
                         ++piece0;
