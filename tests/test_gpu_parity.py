@@ -84,6 +84,32 @@ def test_route_ties_pick_lower_index(H):
     assert H.rel_err(H.host(sh.w), w_ref) < 1e-5
 
 
+@pytest.mark.parametrize("E,k,H_", [(8, 2, 1024), (65, 6, 520), (160, 9, 264)])
+def test_route_near_ties_take_the_exact_path(H, E, k, H_):
+    """Gate rows that differ from one another in a single element by one bf16 step: every gap
+    between logits is far below what fp32 accumulation resolves, yet far above fp64 rounding,
+    so the indices are well defined and any kernel that decides them from approximate logits
+    must fall back to exact ones for (nearly) every token."""
+    cfg = small("c2_mixtral", T=150, H=H_, E=E, k=k, G=1)
+    inp = W.make_layer_inputs(cfg)
+    base = inp["w_gate"][0].astype(np.float32)
+    wg = np.tile(base, (E, 1))
+    for e in range(1, E):
+        j = (7 * e) % H_
+        bits = wg[e, j:j + 1].view(np.uint32)
+        bits += np.uint32((1 + e // H_) << 16)               # next bf16 value(s) away from zero
+    idx_ref, w_ref, z = O.route(inp["x"], wg, None, cfg.k, cfg.renorm)
+    margin = O.route_margin(z, cfg.k)
+    assert margin.max() < 1e-2
+    ok = margin > 1e-9          # bf16 values have few bits, so some products coincide exactly: those tokens are skipped
+    assert ok.mean() > 0.5
+    sh = H.Share(cfg)
+    sh.route(H.dev(inp["x"], cfg.dtype), H.dev(wg, cfg.dtype), None)
+    torch.cuda.synchronize()
+    assert np.array_equal(H.host(sh.idx)[ok], idx_ref[ok])
+    assert H.rel_err(H.host(sh.w)[ok], w_ref[ok]) < 1e-5
+
+
 DISPATCH_CASES = [
     (W.get_config("c1_tiny_fp32"), 0),
     (small("c1_tiny_fp32", T=1, H=4, E=2, k=1, G=2), 0),
