@@ -163,8 +163,8 @@ typedef struct {
 } moe_expert_w;
 
 /* Bytes of device workspace moe_expert_ffn needs for up to R_max rows (the
- * [R,F] intermediate, a tile map and, for bf16, 64 MiB of fp32 partial tiles);
- * 0 if an argument is invalid. */
+ * [R,F] intermediate, a tile map of about 1 KiB per 64 rows plus 1 MiB and, for
+ * bf16, 64 MiB of fp32 partial tiles); 0 if an argument is invalid. */
 size_t moe_ffn_workspace_bytes(int32_t R_max, int32_t H, int32_t F, int32_t act, int32_t dtype);
 
 /* Expert FFN (Sec. 2.1) over the rows this GPU received: rows
@@ -177,6 +177,10 @@ size_t moe_ffn_workspace_bytes(int32_t R_max, int32_t H, int32_t F, int32_t act,
  *   experts     HOST [n_local], n_local <= 64
  *   out         device [R,H] dtype; rows outside every segment are left untouched
  *   workspace   device, >= moe_ffn_workspace_bytes(R,H,F,act,dtype), 256-byte aligned
+ * The segments of one expert need not be adjacent and may be short: bf16 tiles
+ * are filled from all of an expert's segments in index order (as long as
+ * R * max(H,F) * 2 bytes is at most 4 GiB; beyond that only adjacent segments of
+ * an expert share tiles).
  * bf16: H and F must be multiples of 128 and H*F*2 bytes (one weight matrix) at
  * most 4 GiB, else MOE_ESHAPE; the [R,F] intermediate is rounded to bf16 once.
  * fp32: any sizes with H, F multiples of 4. */

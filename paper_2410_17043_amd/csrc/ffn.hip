@@ -35,7 +35,10 @@ struct TileMap {
     int32_t* row0;      // [max_tiles] first row of the tile
     int32_t* nrows;     // [max_tiles] valid rows (1..BM)
     int32_t* expert;    // [max_tiles] local expert
+    int32_t* gather;    // [max_tiles] 0: the tile is rows row0 .. row0 + nrows - 1; 1: row r is row0 + rel[tile][r]
+    int32_t* rel;       // [max_tiles][kRelPitch] row offsets of the gathered tiles (written for those only)
 };
+constexpr int kRelPitch = 256;
 
 struct ExpertTable {
     const void* w1[MOE_MAX_LOCAL];
@@ -45,55 +48,210 @@ struct ExpertTable {
 
 __host__ __device__ inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 inline int max_tiles_for(int R) { return R / 64 + 1 + kMaxSeg; }
-inline size_t tilemap_bytes(int R) { return align256(256 + 3 * sizeof(int32_t) * (size_t)max_tiles_for(R)); }
+inline size_t tilemap_bytes(int R) {
+    return align256(256 + 4 * sizeof(int32_t) * (size_t)max_tiles_for(R)) + (size_t)max_tiles_for(R) * kRelPitch * sizeof(int32_t);
+}
 
 TileMap tilemap_at(void* ws, int R) {
     TileMap m;
     char* p = reinterpret_cast<char*>(ws);
+    const size_t n = (size_t)max_tiles_for(R);
     m.n_tiles = reinterpret_cast<int32_t*>(p);
     m.row0 = reinterpret_cast<int32_t*>(p + 256);
-    m.nrows = m.row0 + max_tiles_for(R);
-    m.expert = m.nrows + max_tiles_for(R);
+    m.nrows = m.row0 + n;
+    m.expert = m.nrows + n;
+    m.gather = m.expert + n;
+    m.rel = reinterpret_cast<int32_t*>(p + align256(256 + 4 * sizeof(int32_t) * n));
     return m;
 }
 
-// One block.  Thread 0 merges adjacent segments of the same expert into runs; all
-// threads then cut the runs into tiles of BM rows.
-__global__ __launch_bounds__(256) void tilemap_kernel(const int32_t* __restrict__ seg_offset,
-                                                      const int32_t* __restrict__ seg_expert, int nseg, int R, int BM,
-                                                      int n_local, TileMap m) {
-    __shared__ int run_lo[kMaxSeg], run_hi[kMaxSeg], run_exp[kMaxSeg], run_tile0[kMaxSeg];
-    __shared__ int n_runs, n_tiles;
-    if (threadIdx.x == 0) {
-        int nr = 0, nt = 0, i = 0;
-        while (i < nseg) {
-            const int e = seg_expert[i];
-            int lo = seg_offset[i], hi = seg_offset[i + 1];
-            int j = i + 1;
-            while (j < nseg && seg_expert[j] == e) { hi = seg_offset[j + 1]; ++j; }
-            i = j;
-            lo = max(lo, 0);
-            hi = min(hi, R);
-            if (hi > lo && e >= 0 && e < n_local) {
-                run_lo[nr] = lo; run_hi[nr] = hi; run_exp[nr] = e; run_tile0[nr] = nt;
-                nt += (hi - lo + BM - 1) / BM;
-                ++nr;
-            }
+// Tile map.  The received rows come as segments (rows seg_offset[i] .. seg_offset[i+1] - 1 belong to local
+// expert seg_expert[i]); with several sources and several local experts the segments of one expert are not
+// adjacent, and a segment can be much shorter than a tile (160 rows per source and expert under the
+// capacity rule of the Switch-shape workload), so cutting every segment into tiles of its own would leave
+// most tiles half empty.  With `gather` the segments of an expert are chained in index order into one
+// list of rows that is cut into full tiles: a tile whose rows are not consecutive in memory carries a
+// table of row offsets (rel), which the GEMM uses for its A-operand addresses and its output rows.
+// Without `gather` only adjacent segments of the same expert are merged (every tile is consecutive rows).
+//
+// Items are the clamped, non-empty segments in processing order; a group is a maximal chain of items of
+// one expert whose rows increase (so offsets from the tile's first row are never negative); tiles never
+// straddle groups.  The construction is written once for the device kernel and for the host self check.
+struct SegWork {
+    int lo[kMaxSeg], hi[kMaxSeg], exp[kMaxSeg];                            // items (rows lo .. hi - 1 of one expert)
+    int v0[kMaxSeg];                                                       // position of the item's first row in its group
+    int grp[kMaxSeg];                                                      // group of the item
+    int g_first[kMaxSeg + 1], g_tile0[kMaxSeg + 1], g_rows[kMaxSeg];       // groups: first item, first tile, rows
+    int raw_off[kMaxSeg + 1], raw_exp[kMaxSeg];                            // the caller's segment list
+    int cnt[MOE_MAX_LOCAL], pos[MOE_MAX_LOCAL];
+    int n_items, n_groups, n_tiles;
+};
+constexpr int kMapThreads = 1024;       // one block; 16 waves hide the LDS latency of the searches below
+
+// The steps below take (tid, nth) = this thread and the thread count; a barrier separates them.
+// 1: an expert outside [0, n_local) (-1) or an empty row range (-2) marks a segment to be skipped
+__host__ __device__ inline void tilemap_clean(SegWork& w, int nseg, int R, int n_local, int tid, int nth) {
+    for (int i = tid; i < nseg; i += nth) {
+        const int lo = w.raw_off[i] > 0 ? w.raw_off[i] : 0;
+        const int hi = w.raw_off[i + 1] < R ? w.raw_off[i + 1] : R;
+        const int e = w.raw_exp[i];
+        if (!(e >= 0 && e < n_local)) w.raw_exp[i] = -1;
+        else if (!(hi > lo)) w.raw_exp[i] = -2;             // no rows: neither an item nor the end of a run
+    }
+    for (int e = tid; e < n_local; e += nth) w.cnt[e] = 0;
+}
+// 2 (gather): rank of every segment among the segments of its expert, and the count per expert
+__host__ __device__ inline void tilemap_rank(SegWork& w, int nseg, int tid, int nth) {
+    for (int i = tid; i < nseg; i += nth) {
+        const int e = w.raw_exp[i];
+        if (e < 0) continue;
+        int rank = 0, total = 0;
+        for (int j = 0; j < nseg; ++j) {
+            const int same = (w.raw_exp[j] == e) ? 1 : 0;
+            total += same;
+            rank += (j < i) ? same : 0;
         }
-        n_runs = nr;
-        n_tiles = nt;
-        *m.n_tiles = nt;
+        w.v0[i] = rank;                              // parked here until step 4
+        w.cnt[e] = total;                            // every segment of e writes the same value
+    }
+}
+// 3 (gather, one thread): where the items of every expert start
+__host__ __device__ inline void tilemap_starts(SegWork& w, int n_local) {
+    int p = 0;
+    for (int e = 0; e < n_local; ++e) { w.pos[e] = p; p += w.cnt[e]; }
+    w.n_items = p;
+}
+// 4 (gather): segment i becomes item pos[e] + rank
+__host__ __device__ inline void tilemap_place(SegWork& w, int nseg, int R, int tid, int nth) {
+    for (int i = tid; i < nseg; i += nth) {
+        const int e = w.raw_exp[i];
+        if (e < 0) continue;
+        const int k = w.pos[e] + w.v0[i];
+        w.lo[k] = w.raw_off[i] > 0 ? w.raw_off[i] : 0;
+        w.hi[k] = w.raw_off[i + 1] < R ? w.raw_off[i + 1] : R;
+        w.exp[k] = e;
+    }
+}
+// 2-4 without gathering (one thread): adjacent segments of the same expert merged
+__host__ __device__ inline void tilemap_merge(SegWork& w, int nseg, int R) {
+    int ni = 0, i = 0;
+    while (i < nseg) {
+        const int e = w.raw_exp[i];
+        if (e < 0) { ++i; continue; }
+        int j = i + 1;
+        while (j < nseg && (w.raw_exp[j] == e || w.raw_exp[j] == -2)) ++j;
+        const int lo = w.raw_off[i] > 0 ? w.raw_off[i] : 0;
+        const int hi = w.raw_off[j] < R ? w.raw_off[j] : R;
+        if (hi > lo) { w.lo[ni] = lo; w.hi[ni] = hi; w.exp[ni] = e; ++ni; }
+        i = j;
+    }
+    w.n_items = ni;
+}
+// 5 (one thread): groups and their tiles; the running sums stay in registers so the loads of the loop overlap
+__host__ __device__ inline void tilemap_groups(SegWork& w, int BM, bool gather, int max_tiles) {
+    const int ni = w.n_items;
+    int ng = 0, nt = 0, rows = 0, prev_exp = -1, prev_hi = 0;
+    for (int k = 0; k < ni; ++k) {
+        const int lo = w.lo[k], hi = w.hi[k], e = w.exp[k];
+        const bool chained = gather && k > 0 && e == prev_exp && lo >= prev_hi;
+        if (!chained) {
+            if (ng > 0) { w.g_rows[ng - 1] = rows; nt += (rows + BM - 1) / BM; }
+            w.g_first[ng] = k; w.g_tile0[ng] = nt; rows = 0;
+            ++ng;
+        }
+        w.v0[k] = rows;
+        w.grp[k] = ng - 1;
+        rows += hi - lo;
+        prev_exp = e; prev_hi = hi;
+    }
+    if (ng > 0) { w.g_rows[ng - 1] = rows; nt += (rows + BM - 1) / BM; }
+    w.g_first[ng] = ni; w.g_tile0[ng] = nt;
+    w.n_groups = ng;
+    // a well-formed list (non-decreasing offsets) stays below the bound; overlapping segments are cut off here
+    w.n_tiles = nt < max_tiles ? nt : max_tiles;
+}
+
+// 6: the record of tile t
+__host__ __device__ inline void tilemap_tile(const SegWork& w, int t, int BM, const TileMap& m) {
+    int a = 0, b = w.n_groups;                       // largest group with g_tile0 <= t
+    while (b - a > 1) { const int mid = (a + b) >> 1; if (w.g_tile0[mid] <= t) a = mid; else b = mid; }
+    const int v_lo = (t - w.g_tile0[a]) * BM;
+    const int v_hi = w.g_rows[a] < v_lo + BM ? w.g_rows[a] : v_lo + BM;
+    int c = w.g_first[a], d = w.g_first[a + 1];      // largest item of the group with v0 <= v_lo
+    while (d - c > 1) { const int mid = (c + d) >> 1; if (w.v0[mid] <= v_lo) c = mid; else d = mid; }
+    bool consecutive = true;
+    for (int k = c; w.v0[k] + (w.hi[k] - w.lo[k]) < v_hi; ++k)
+        if (w.lo[k + 1] != w.hi[k]) consecutive = false;
+    m.row0[t] = w.lo[c] + (v_lo - w.v0[c]);
+    m.nrows[t] = v_hi - v_lo;
+    m.expert[t] = w.exp[c];
+    m.gather[t] = consecutive ? 0 : 1;
+}
+// 7: the offset tables.  A tile has a gap exactly where an item starts inside it (not at its first row)
+// whose rows do not follow the previous item's; the FIRST such item of a tile fills the table of the tile.
+struct RelJob { int tile, v_lo, v_hi, first_item, row0; };
+__host__ __device__ inline bool tilemap_rel_job(const SegWork& w, int k, int BM, RelJob* job) {
+    const int g = w.grp[k];
+    if (k == w.g_first[g] || w.lo[k] == w.hi[k - 1]) return false;       // no gap in front of this item
+    const int v_lo = (w.v0[k] / BM) * BM;
+    if (w.v0[k] == v_lo) return false;                                    // the gap falls between two tiles
+    int c = k - 1;                                                        // walk back to the tile's first item
+    while (w.v0[c] > v_lo) {
+        if (w.lo[c] != w.hi[c - 1]) return false;                         // an earlier item owns this tile
+        --c;
+    }
+    job->tile = w.g_tile0[g] + v_lo / BM;
+    job->v_lo = v_lo;
+    job->v_hi = w.g_rows[g] < v_lo + BM ? w.g_rows[g] : v_lo + BM;
+    job->first_item = c;
+    job->row0 = w.lo[c] + (v_lo - w.v0[c]);
+    return true;
+}
+__host__ __device__ inline int tilemap_rel(const SegWork& w, const RelJob& job, int r) {
+    const int v = job.v_lo + r;
+    int c = job.first_item;
+    while (w.v0[c] + (w.hi[c] - w.lo[c]) <= v) ++c;
+    return w.lo[c] + (v - w.v0[c]) - job.row0;
+}
+
+// One block.  All threads copy the segment list into LDS (one round trip to memory instead of one per
+// segment) and put it in order; thread 0 forms the groups; then one thread per tile writes the tile
+// records and one wave per gap fills the offset table of the tile it lies in, 64 rows at a time.
+__global__ __launch_bounds__(kMapThreads) void tilemap_kernel(const int32_t* __restrict__ seg_offset,
+                                                              const int32_t* __restrict__ seg_expert, int nseg, int R,
+                                                              int BM, int n_local, int gather, int max_tiles, TileMap m) {
+    __shared__ SegWork w;
+    const int tid = threadIdx.x;
+    for (int i = tid; i <= nseg; i += kMapThreads) {
+        w.raw_off[i] = seg_offset[i];
+        if (i < nseg) w.raw_exp[i] = seg_expert[i];
     }
     __syncthreads();
-    for (int r = 0; r < n_runs; ++r) {
-        const int lo = run_lo[r], hi = run_hi[r];
-        const int cnt = (hi - lo + BM - 1) / BM;
-        for (int t = threadIdx.x; t < cnt; t += 256) {
-            const int id = run_tile0[r] + t;
-            m.row0[id] = lo + t * BM;
-            m.nrows[id] = min(BM, hi - (lo + t * BM));
-            m.expert[id] = run_exp[r];
-        }
+    tilemap_clean(w, nseg, R, n_local, tid, kMapThreads);
+    __syncthreads();
+    if (gather) {
+        tilemap_rank(w, nseg, tid, kMapThreads);
+        __syncthreads();
+        if (tid == 0) tilemap_starts(w, n_local);
+        __syncthreads();
+        tilemap_place(w, nseg, R, tid, kMapThreads);
+        __syncthreads();
+    }
+    if (tid == 0) {
+        if (!gather) tilemap_merge(w, nseg, R);
+        tilemap_groups(w, BM, gather != 0, max_tiles);
+        *m.n_tiles = w.n_tiles;
+    }
+    __syncthreads();
+    const int nt = w.n_tiles;
+    for (int t = tid; t < nt; t += kMapThreads) tilemap_tile(w, t, BM, m);
+    if (!gather) return;
+    const int lane = tid & 63, wave = tid >> 6;
+    for (int k = wave; k < w.n_items; k += kMapThreads / 64) {
+        RelJob job;
+        if (!tilemap_rel_job(w, k, BM, &job) || job.tile >= nt) continue;
+        for (int r = lane; r < job.v_hi - job.v_lo; r += 64)
+            m.rel[(size_t)job.tile * kRelPitch + r] = tilemap_rel(w, job, r);
     }
 }
 
@@ -323,9 +481,9 @@ __device__ __forceinline__ void stage_rows(const f32x16 (&acc_i)[4], int i, unsi
             *reinterpret_cast<u32x2*>(region + (i * 32 + fr) * G::PITCH + (j * 32 + g * 8 + fk * 4) * 2) = p;
         }
 }
-template <int EPI>
-__device__ __forceinline__ void flush_rows(int i_lo, int i_hi, const unsigned char* lds, int row0, int nrows, int n0, int N,
-                                           uint16_t* __restrict__ C, int ldc) {
+template <int EPI, bool GATHER>
+__device__ __forceinline__ void flush_rows_impl(int i_lo, int i_hi, const unsigned char* lds, int row0, int nrows,
+                                                const int32_t* __restrict__ rel, int n0, int N, uint16_t* __restrict__ C, int ldc) {
     using G = EpiGeom<EPI>;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -346,9 +504,17 @@ __device__ __forceinline__ void flush_rows(int i_lo, int i_hi, const unsigned ch
         const int gr = wm * 128 + r;
         if (gr < nrows && col < N) {
             const u32x4 q = {lo.x, lo.y, hi.x, hi.y};
-            *reinterpret_cast<u32x4*>(C + (size_t)(row0 + gr) * ldc + col) = q;
+            const int orow = row0 + (GATHER ? rel[gr] : gr);   // gathered tile: its rows are not consecutive
+            *reinterpret_cast<u32x4*>(C + (size_t)orow * ldc + col) = q;
         }
     }
+}
+// two copies of the store loop: the common one keeps its plain row arithmetic
+template <int EPI>
+__device__ __forceinline__ void flush_rows(int i_lo, int i_hi, const unsigned char* lds, int row0, int nrows,
+                                           const int32_t* __restrict__ rel, int n0, int N, uint16_t* __restrict__ C, int ldc) {
+    if (rel) flush_rows_impl<EPI, true>(i_lo, i_hi, lds, row0, nrows, rel, n0, N, C, ldc);
+    else flush_rows_impl<EPI, false>(i_lo, i_hi, lds, row0, nrows, rel, n0, N, C, ldc);
 }
 
 // C[r, n] = epi(sum_k A[r,k] B0[n,k] , sum_k A[r,k] B1[n,k]) for one 256-row M-tile and one
@@ -387,6 +553,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
     const int row0 = __builtin_amdgcn_readfirstlane(m.row0[tile_m]);
     const int nrows = __builtin_amdgcn_readfirstlane(m.nrows[tile_m]);
     const int ex = __builtin_amdgcn_readfirstlane(m.expert[tile_m]);
+    const int32_t* rel = __builtin_amdgcn_readfirstlane(m.gather[tile_m]) ? m.rel + (size_t)tile_m * kRelPitch : nullptr;
     auto pick = [&](int which) -> const uint16_t* {
         return reinterpret_cast<const uint16_t*>(which == 0 ? tab.w1[ex] : which == 1 ? tab.w_up[ex] : tab.w_down[ex]);
     };
@@ -414,7 +581,9 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
     for (int i = 0; i < 4; ++i) {
         const int blk = wave + 4 * i;                        // 16-row block of the tile (wave-uniform)
         const int r = blk * 16 + lr;                         // tile row this lane fetches
-        a_voff[i] = (uint32_t)min(r, nrows - 1) * (uint32_t)lda * 2u + (uint32_t)lc * 16u;
+        int ar = min(r, nrows - 1);
+        if (rel) ar = rel[ar];                               // offsets from row0, below 2^32 bytes (checked on the host)
+        a_voff[i] = (uint32_t)ar * (uint32_t)lda * 2u + (uint32_t)lc * 16u;
         int col;
         if (EPI == EPI_SWIGLU) {
             const int w = r >> 7, sub = r & 127;
@@ -570,7 +739,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) stage_rows<EPI>(acc[i], i, lds);
-    flush_rows<EPI>(0, 4, lds, row0, nrows, n0, N, C, ldc);
+    flush_rows<EPI>(0, 4, lds, row0, nrows, rel, n0, N, C, ldc);
 }
 
 // Adds the pieces of one 32-row tile per wave (blockIdx.x % 4) of tail tile blockIdx.x / 4 in piece
@@ -587,6 +756,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_tail_kernel(TileMap m, int N, i
     int tile_m, tile_n;
     tile_of_block(plan.n_full + tt, total, n_tiles_m, tiles_n, &tile_m, &tile_n);
     const int row0 = m.row0[tile_m], nrows = m.nrows[tile_m];
+    const int32_t* rel = m.gather[tile_m] ? m.rel + (size_t)tile_m * kRelPitch : nullptr;
     const int tid = threadIdx.x;
     const f32x4* src = reinterpret_cast<const f32x4*>(reinterpret_cast<const char*>(partial) +
                                                       (size_t)tt * plan.parts * kPartialBytes) + (size_t)i * 16 * 256 + tid;
@@ -617,7 +787,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_tail_kernel(TileMap m, int N, i
 #pragma unroll
             for (int t = 0; t < 4; ++t) acc_i[j][4 * q + t] = sum[j * 4 + q][t];
     stage_rows<EPI>(acc_i, i, lds);
-    flush_rows<EPI>(i, i + 1, lds, row0, nrows, tile_n * EpiGeom<EPI>::NOUT, N, C, ldc);
+    flush_rows<EPI>(i, i + 1, lds, row0, nrows, rel, tile_n * EpiGeom<EPI>::NOUT, N, C, ldc);
 }
 
 constexpr int kMaxCU = 256;                    // tail pieces per launch, at most: sizes the partial-tile workspace
@@ -703,6 +873,76 @@ extern "C" int moe_selfcheck_tile_order(int32_t tiles_m, int32_t tiles_n, int32_
     return p.parts;
 }
 
+// Host-side self check of the tile map (not part of the published interface; used by the CPU tests): runs
+// the steps that the device kernel runs, on the host, and verifies that every row of every non-empty
+// segment of a known expert lies in exactly one tile of that expert, that tile rows increase, that exactly
+// the tiles with gaps are marked as gathered and that their offset tables are complete.  Returns the
+// number of tiles, or a negative status.
+extern "C" int moe_selfcheck_tile_map(const int32_t* seg_offset, const int32_t* seg_expert, int32_t nseg, int32_t R,
+                                      int32_t bm, int32_t n_local, int32_t gather) {
+    if (!seg_offset || !seg_expert || nseg < 0 || nseg > kMaxSeg || R < 0 || bm < 1 || bm > kRelPitch || n_local < 1 || n_local > MOE_MAX_LOCAL)
+        return moe_set_error(MOE_EINVAL, "moe_selfcheck_tile_map: bad argument");
+    std::vector<SegWork> store(1);
+    SegWork& w = store[0];
+    for (int i = 0; i <= nseg; ++i) w.raw_off[i] = seg_offset[i];
+    for (int i = 0; i < nseg; ++i) w.raw_exp[i] = seg_expert[i];
+    const int nth = 7;                                    // any thread count and order must give the same map
+    for (int t = 0; t < nth; ++t) tilemap_clean(w, nseg, R, n_local, t, nth);
+    if (gather) {
+        for (int t = nth - 1; t >= 0; --t) tilemap_rank(w, nseg, t, nth);
+        tilemap_starts(w, n_local);
+        for (int t = 0; t < nth; ++t) tilemap_place(w, nseg, R, t, nth);
+    } else {
+        tilemap_merge(w, nseg, R);
+    }
+    const int max_tiles = (R + bm - 1) / bm + nseg;
+    tilemap_groups(w, bm, gather != 0, max_tiles + 1);
+    const int nt = w.n_tiles;
+    if (nt > max_tiles) return moe_set_error(MOE_EINTERNAL, "%d tiles exceed the bound %d", nt, max_tiles);
+    std::vector<int32_t> row0(nt), nrows(nt), expert(nt), gat(nt), rel((size_t)nt * kRelPitch, -1);
+    int32_t n_tiles = nt;
+    TileMap m{&n_tiles, row0.data(), nrows.data(), expert.data(), gat.data(), rel.data()};
+    for (int t = nt - 1; t >= 0; --t) tilemap_tile(w, t, bm, m);
+    std::vector<int> filled(nt, 0);
+    for (int k = 0; k < w.n_items; ++k) {
+        RelJob job;
+        if (!tilemap_rel_job(w, k, bm, &job)) continue;
+        if (job.tile < 0 || job.tile >= nt) return moe_set_error(MOE_EINTERNAL, "offset table for tile %d of %d", job.tile, nt);
+        if (job.row0 != row0[job.tile] || job.v_hi - job.v_lo != nrows[job.tile]) return moe_set_error(MOE_EINTERNAL, "tile %d: table and record disagree", job.tile);
+        ++filled[job.tile];
+        for (int r = 0; r < job.v_hi - job.v_lo; ++r) rel[(size_t)job.tile * kRelPitch + r] = tilemap_rel(w, job, r);
+    }
+    std::vector<int> owner((size_t)R, -1);
+    for (int i = 0; i < nseg; ++i) {
+        const int lo = std::max(seg_offset[i], 0), hi = std::min(seg_offset[i + 1], R);
+        if (hi > lo && seg_expert[i] >= 0 && seg_expert[i] < n_local)
+            for (int r = lo; r < hi; ++r) owner[r] = seg_expert[i];
+    }
+    std::vector<int> hits((size_t)R, 0);
+    for (int t = 0; t < nt; ++t) {
+        if (nrows[t] < 1 || nrows[t] > bm) return moe_set_error(MOE_EINTERNAL, "tile %d has %d rows", t, nrows[t]);
+        if (gat[t] && !gather) return moe_set_error(MOE_EINTERNAL, "tile %d is gathered but gathering is off", t);
+        if (filled[t] != (gat[t] ? 1 : 0)) return moe_set_error(MOE_EINTERNAL, "tile %d: gather flag %d, table filled %d times", t, gat[t], filled[t]);
+        int prev = -1;
+        bool gaps = false;
+        for (int r = 0; r < nrows[t]; ++r) {
+            const int off = gat[t] ? rel[(size_t)t * kRelPitch + r] : r;
+            const int row = row0[t] + off;
+            if (off < 0 || row < 0 || row >= R) return moe_set_error(MOE_EINTERNAL, "tile %d row %d maps to %d", t, r, row);
+            if (r == 0 && off != 0) return moe_set_error(MOE_EINTERNAL, "tile %d does not start at its first row", t);
+            if (row <= prev) return moe_set_error(MOE_EINTERNAL, "tile %d: rows do not increase", t);
+            if (prev >= 0 && row != prev + 1) gaps = true;
+            if (owner[row] != expert[t]) return moe_set_error(MOE_EINTERNAL, "tile %d of expert %d holds row %d of expert %d", t, expert[t], row, owner[row]);
+            ++hits[row];
+            prev = row;
+        }
+        if (gaps != (gat[t] != 0)) return moe_set_error(MOE_EINTERNAL, "tile %d: gather flag %d but gaps %d", t, gat[t], (int)gaps);
+    }
+    for (int r = 0; r < R; ++r)
+        if (hits[r] != (owner[r] >= 0 ? 1 : 0)) return moe_set_error(MOE_EINTERNAL, "row %d is in %d tiles", r, hits[r]);
+    return nt;
+}
+
 extern "C" size_t moe_ffn_workspace_bytes(int32_t R_max, int32_t H, int32_t F, int32_t act, int32_t dtype) {
     if (R_max < 0 || H <= 0 || F <= 0 || act < 0 || act > 2 || (dtype != MOE_F32 && dtype != MOE_BF16)) return 0;
     const size_t partial = (dtype == MOE_BF16) ? (size_t)kMaxCU * kPartialBytes : 0;   // pieces of tail tiles
@@ -749,7 +989,10 @@ static int ffn_impl(const void* recv, int32_t R, const int32_t* seg_offset, cons
     float* partial = reinterpret_cast<float*>(reinterpret_cast<char*>(hmid) + align256((size_t)R * F * elem_size(dtype)));
     const int bm = (dtype == MOE_BF16) ? BM : 64;
     if (ev) MOE_HIP(hipEventRecord(ev[0], st));
-    hipLaunchKernelGGL(tilemap_kernel, dim3(1), dim3(256), 0, st, seg_offset, seg_expert, nseg, R, bm, n_local, m);
+    // gathered tiles address their rows by 32-bit byte offsets from the tile's first row
+    const int gather = (dtype == MOE_BF16 && (size_t)R * (size_t)std::max(H, F) * 2 <= 0xFFFFFFFFull) ? 1 : 0;
+    hipLaunchKernelGGL(tilemap_kernel, dim3(1), dim3(kMapThreads), 0, st, seg_offset, seg_expert, nseg, R, bm, n_local, gather,
+                       (R + bm - 1) / bm + nseg, m);
     MOE_LAUNCH_CHECK("tilemap_kernel");
     if (ev) MOE_HIP(hipEventRecord(ev[1], st));
     int rc;

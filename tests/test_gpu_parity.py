@@ -280,6 +280,11 @@ FFN_CASES = [
     # a last round that is between a quarter and half full: two and three pieces of 64 k-tiles
     ("bf16", 2, 700, 4096, 4608, 1, 1),
     ("bf16", 2, 500, 6144, 5120, 1, 1),
+    # many short segments with the experts interleaved (several sources, several local experts): tiles
+    # gather rows from all segments of an expert
+    ("bf16", 1, 2000, 256, 512, 4, 64),
+    ("bf16", 2, 1500, 384, 256, 3, 200),
+    ("bf16", 0, 900, 2048, 2304, 2, 31),                   # with pieces along K as well
 ]
 
 

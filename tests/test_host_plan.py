@@ -282,3 +282,57 @@ def test_tile_order_and_tail_plan_cover_every_tile_once():
     assert lib.moe_selfcheck_tile_order(81, 112, 256, 128) == 2       # first GEMM of the Mixtral-shape share
     assert lib.moe_selfcheck_tile_order(81, 16, 256, 448) == 8        # second GEMM
     assert lib.moe_selfcheck_tile_order(0, 4, 256, 8) < 0
+
+
+def test_tile_map_gathers_the_segments_of_an_expert():
+    """The FFN's tile map, built on the host by the library's own self check (which verifies that every row
+    lies in exactly one tile of its expert): with gathering the tile count is what the rows per expert
+    need, however the segments interleave; without it, what the runs of adjacent segments need."""
+    import ctypes as C
+    from paper_2410_17043_amd import _lib
+    lib = _lib.load()
+    fn = lib.moe_selfcheck_tile_map
+    fn.restype = C.c_int
+    fn.argtypes = [C.POINTER(C.c_int32), C.POINTER(C.c_int32)] + [C.c_int32] * 5
+
+    def run(lens, experts, n_local, bm, gather, R=None):
+        off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        ex = np.asarray(experts, dtype=np.int32)
+        R = int(off[-1]) if R is None else R
+        rc = fn(off.ctypes.data_as(C.POINTER(C.c_int32)), ex.ctypes.data_as(C.POINTER(C.c_int32)), len(lens), R, bm,
+                n_local, gather)
+        assert rc >= 0, lib.moe_last_error()
+        return rc
+
+    def need(lens, experts, n_local, bm, gather):
+        if gather:
+            return sum(-(-sum(l for l, e in zip(lens, experts) if e == x) // bm) for x in range(n_local))
+        segs = [(l, e) for l, e in zip(lens, experts) if l > 0 or not 0 <= e < n_local]   # empty segments do not count
+        total, i = 0, 0
+        while i < len(segs):
+            j = i
+            while j < len(segs) and segs[j][1] == segs[i][1]:
+                j += 1
+            if 0 <= segs[i][1] < n_local:
+                total += -(-sum(l for l, _ in segs[i:j]) // bm)
+            i = j
+        return total
+
+    # the Switch-shape share: 16 sources x 4 local experts, at most 160 rows each (the capacity)
+    lens = [160, 160, 150, 97] * 16
+    experts = [0, 1, 2, 3] * 16
+    assert run(lens, experts, 4, 256, 1) == need(lens, experts, 4, 256, 1) == 10 + 10 + 10 + 7
+    assert run(lens, experts, 4, 256, 0) == 64
+    r = np.random.default_rng(5)
+    for _ in range(300):
+        nseg = int(r.integers(0, 60))
+        n_local = int(r.integers(1, 9))
+        bm = int(r.choice([64, 256]))
+        lens = [int(v) for v in r.choice([0, 1, 3, 100, 255, 256, 257, 700], size=nseg)]
+        experts = [int(v) for v in r.integers(-1, n_local + 1, size=nseg)]       # -1 and n_local: skipped
+        for gather in (0, 1):
+            assert run(lens, experts, n_local, bm, gather) == need(lens, experts, n_local, bm, gather)
+    # offsets past R are clamped; 1024 segments of one row each
+    assert run([10, 10, 10], [0, 1, 0], 2, 256, 1, R=25) == 2
+    assert run([1] * 1024, [i % 3 for i in range(1024)], 3, 256, 1) == 2 + 2 + 2
+    assert run([1] * 1024, [i % 3 for i in range(1024)], 3, 256, 0) == 1024
