@@ -24,6 +24,7 @@
 // fp32 path (correctness configuration): plain 64x64x16 LDS-tiled vector-ALU GEMM.
 #include "common.h"
 #include <algorithm>
+#include <cstddef>
 #include <vector>
 
 namespace {
@@ -81,14 +82,17 @@ struct SegWork {
     int lo[kMaxSeg], hi[kMaxSeg], exp[kMaxSeg];                            // items (rows lo .. hi - 1 of one expert)
     int v0[kMaxSeg];                                                       // position of the item's first row in its group
     int grp[kMaxSeg];                                                      // group of the item
+    int gaps[kMaxSeg];                                                     // items up to and including this one that do not follow their predecessor in memory
     int g_first[kMaxSeg + 1], g_tile0[kMaxSeg + 1], g_rows[kMaxSeg];       // groups: first item, first tile, rows
-    int raw_off[kMaxSeg + 1], raw_exp[kMaxSeg];                            // the caller's segment list
+    int raw_off[kMaxSeg + 1], raw_exp[kMaxSeg];                            // the caller's segment list (raw_off: scratch once the items exist)
     int cnt[MOE_MAX_LOCAL], pos[MOE_MAX_LOCAL];
     int n_items, n_groups, n_tiles;
 };
-constexpr int kMapThreads = 1024;       // one block; 16 waves hide the LDS latency of the searches below
+constexpr int kMapThreads = 1024;       // one block: a thread per segment / item, 16 waves to hide the LDS latency of the searches
 
-// The steps below take (tid, nth) = this thread and the thread count; a barrier separates them.
+// The steps take (tid, nth) = this thread and the thread count where they run in parallel; a barrier
+// separates them.  The host self check runs the same per-element functions with plain loops in place
+// of the block-wide ballots and prefix sums of the device kernel.
 // 1: an expert outside [0, n_local) (-1) or an empty row range (-2) marks a segment to be skipped
 __host__ __device__ inline void tilemap_clean(SegWork& w, int nseg, int R, int n_local, int tid, int nth) {
     for (int i = tid; i < nseg; i += nth) {
@@ -100,23 +104,16 @@ __host__ __device__ inline void tilemap_clean(SegWork& w, int nseg, int R, int n
     }
     for (int e = tid; e < n_local; e += nth) w.cnt[e] = 0;
 }
-// 2 (gather): rank of every segment among the segments of its expert, and the count per expert
-__host__ __device__ inline void tilemap_rank(SegWork& w, int nseg, int tid, int nth) {
-    for (int i = tid; i < nseg; i += nth) {
+// 2 (gather), host form: rank of every segment among the segments of its expert, and the count per expert
+inline void tilemap_rank_host(SegWork& w, int nseg) {
+    for (int i = 0; i < nseg; ++i) {
         const int e = w.raw_exp[i];
         if (e < 0) continue;
-        int rank = 0, total = 0;
-        for (int j = 0; j < nseg; ++j) {
-            const int same = (w.raw_exp[j] == e) ? 1 : 0;
-            total += same;
-            rank += (j < i) ? same : 0;
-        }
-        w.v0[i] = rank;                              // parked here until step 4
-        w.cnt[e] = total;                            // every segment of e writes the same value
+        w.v0[i] = w.cnt[e]++;                        // the rank is parked in v0 until step 4
     }
 }
-// 3 (gather, one thread): where the items of every expert start
-__host__ __device__ inline void tilemap_starts(SegWork& w, int n_local) {
+// 3 (gather), host form: where the items of every expert start
+inline void tilemap_starts_host(SegWork& w, int n_local) {
     int p = 0;
     for (int e = 0; e < n_local; ++e) { w.pos[e] = p; p += w.cnt[e]; }
     w.n_items = p;
@@ -147,111 +144,245 @@ __host__ __device__ inline void tilemap_merge(SegWork& w, int nseg, int R) {
     }
     w.n_items = ni;
 }
-// 5 (one thread): groups and their tiles; the running sums stay in registers so the loads of the loop overlap
-__host__ __device__ inline void tilemap_groups(SegWork& w, int BM, bool gather, int max_tiles) {
+// 5: does item k open a group / does it leave a gap behind its predecessor
+__host__ __device__ inline bool tilemap_opens(const SegWork& w, int k, bool gather) {
+    return !(gather && k > 0 && w.exp[k] == w.exp[k - 1] && w.lo[k] >= w.hi[k - 1]);
+}
+__host__ __device__ inline bool tilemap_gap(const SegWork& w, int k, bool gather) {
+    return !tilemap_opens(w, k, gather) && w.lo[k] != w.hi[k - 1];
+}
+// 5, host form: groups and their tiles
+inline void tilemap_groups_host(SegWork& w, int BM, bool gather) {
     const int ni = w.n_items;
-    int ng = 0, nt = 0, rows = 0, prev_exp = -1, prev_hi = 0;
+    int ng = 0, nt = 0, rows = 0, gaps = 0;
     for (int k = 0; k < ni; ++k) {
-        const int lo = w.lo[k], hi = w.hi[k], e = w.exp[k];
-        const bool chained = gather && k > 0 && e == prev_exp && lo >= prev_hi;
-        if (!chained) {
+        if (tilemap_opens(w, k, gather)) {
             if (ng > 0) { w.g_rows[ng - 1] = rows; nt += (rows + BM - 1) / BM; }
             w.g_first[ng] = k; w.g_tile0[ng] = nt; rows = 0;
             ++ng;
         }
+        gaps += tilemap_gap(w, k, gather) ? 1 : 0;
+        w.gaps[k] = gaps;
         w.v0[k] = rows;
         w.grp[k] = ng - 1;
-        rows += hi - lo;
-        prev_exp = e; prev_hi = hi;
+        rows += w.hi[k] - w.lo[k];
     }
     if (ng > 0) { w.g_rows[ng - 1] = rows; nt += (rows + BM - 1) / BM; }
     w.g_first[ng] = ni; w.g_tile0[ng] = nt;
     w.n_groups = ng;
-    // a well-formed list (non-decreasing offsets) stays below the bound; overlapping segments are cut off here
-    w.n_tiles = nt < max_tiles ? nt : max_tiles;
+    w.n_tiles = nt;
 }
 
+// item of group g that holds group row v: the largest item with v0 <= v
+__host__ __device__ inline int tilemap_item_of(const SegWork& w, int g, int v) {
+    int c = w.g_first[g], d = w.g_first[g + 1];
+    while (d - c > 1) { const int mid = (c + d) >> 1; if (w.v0[mid] <= v) c = mid; else d = mid; }
+    return c;
+}
+struct TileSpan { int v_lo, v_hi, first_item, row0, gather; };
+// tile q of group g: its range of group rows, its first row in memory, whether its rows have gaps
+__host__ __device__ inline TileSpan tilemap_span(const SegWork& w, int g, int q, int BM) {
+    TileSpan s;
+    s.v_lo = q * BM;
+    s.v_hi = w.g_rows[g] < s.v_lo + BM ? w.g_rows[g] : s.v_lo + BM;
+    s.first_item = tilemap_item_of(w, g, s.v_lo);
+    const int last_item = tilemap_item_of(w, g, s.v_hi - 1);
+    s.row0 = w.lo[s.first_item] + (s.v_lo - w.v0[s.first_item]);
+    s.gather = (w.gaps[last_item] - w.gaps[s.first_item] > 0) ? 1 : 0;   // a gap in front of an item that starts inside the tile
+    return s;
+}
 // 6: the record of tile t
 __host__ __device__ inline void tilemap_tile(const SegWork& w, int t, int BM, const TileMap& m) {
     int a = 0, b = w.n_groups;                       // largest group with g_tile0 <= t
     while (b - a > 1) { const int mid = (a + b) >> 1; if (w.g_tile0[mid] <= t) a = mid; else b = mid; }
-    const int v_lo = (t - w.g_tile0[a]) * BM;
-    const int v_hi = w.g_rows[a] < v_lo + BM ? w.g_rows[a] : v_lo + BM;
-    int c = w.g_first[a], d = w.g_first[a + 1];      // largest item of the group with v0 <= v_lo
-    while (d - c > 1) { const int mid = (c + d) >> 1; if (w.v0[mid] <= v_lo) c = mid; else d = mid; }
-    bool consecutive = true;
-    for (int k = c; w.v0[k] + (w.hi[k] - w.lo[k]) < v_hi; ++k)
-        if (w.lo[k + 1] != w.hi[k]) consecutive = false;
-    m.row0[t] = w.lo[c] + (v_lo - w.v0[c]);
-    m.nrows[t] = v_hi - v_lo;
-    m.expert[t] = w.exp[c];
-    m.gather[t] = consecutive ? 0 : 1;
+    const TileSpan s = tilemap_span(w, a, t - w.g_tile0[a], BM);
+    m.row0[t] = s.row0;
+    m.nrows[t] = s.v_hi - s.v_lo;
+    m.expert[t] = w.exp[s.first_item];
+    m.gather[t] = s.gather;
 }
-// 7: the offset tables.  A tile has a gap exactly where an item starts inside it (not at its first row)
-// whose rows do not follow the previous item's; the FIRST such item of a tile fills the table of the tile.
-struct RelJob { int tile, v_lo, v_hi, first_item, row0; };
-__host__ __device__ inline bool tilemap_rel_job(const SegWork& w, int k, int BM, RelJob* job) {
-    const int g = w.grp[k];
-    if (k == w.g_first[g] || w.lo[k] == w.hi[k - 1]) return false;       // no gap in front of this item
-    const int v_lo = (w.v0[k] / BM) * BM;
-    if (w.v0[k] == v_lo) return false;                                    // the gap falls between two tiles
-    int c = k - 1;                                                        // walk back to the tile's first item
-    while (w.v0[c] > v_lo) {
-        if (w.lo[c] != w.hi[c - 1]) return false;                         // an earlier item owns this tile
-        --c;
+// 7: the offset tables, item by item.  Only the first and the last tile of an item can have gaps (the
+// tiles in between lie inside the item); for each of the two, if it has gaps, the item's rows in it are a
+// run of consecutive table entries with consecutive values: rel[dst + r] = val + r for r < cnt.
+struct RelJob { int dst, cnt, val; };
+__host__ __device__ inline void tilemap_rel_jobs(const SegWork& w, int k, int BM, int n_tiles, RelJob (&job)[2]) {
+    job[0].cnt = job[1].cnt = 0;
+    const int g = w.grp[k], len = w.hi[k] - w.lo[k];
+    const int q_a = w.v0[k] / BM, q_b = (w.v0[k] + len - 1) / BM;
+    for (int pass = 0; pass < 2; ++pass) {
+        const int q = pass == 0 ? q_a : q_b;
+        if (pass == 1 && q_b == q_a) break;
+        const int tile = w.g_tile0[g] + q;
+        if (tile >= n_tiles) continue;
+        const TileSpan s = tilemap_span(w, g, q, BM);
+        if (!s.gather) continue;
+        const int v_a = w.v0[k] > s.v_lo ? w.v0[k] : s.v_lo;                 // the item's rows inside the tile
+        const int v_b = w.v0[k] + len < s.v_hi ? w.v0[k] + len : s.v_hi;
+        job[pass].dst = tile * kRelPitch + (v_a - s.v_lo);
+        job[pass].cnt = v_b - v_a;
+        job[pass].val = w.lo[k] + (v_a - w.v0[k]) - s.row0;
     }
-    job->tile = w.g_tile0[g] + v_lo / BM;
-    job->v_lo = v_lo;
-    job->v_hi = w.g_rows[g] < v_lo + BM ? w.g_rows[g] : v_lo + BM;
-    job->first_item = c;
-    job->row0 = w.lo[c] + (v_lo - w.v0[c]);
-    return true;
-}
-__host__ __device__ inline int tilemap_rel(const SegWork& w, const RelJob& job, int r) {
-    const int v = job.v_lo + r;
-    int c = job.first_item;
-    while (w.v0[c] + (w.hi[c] - w.lo[c]) <= v) ++c;
-    return w.lo[c] + (v - w.v0[c]) - job.row0;
 }
 
-// One block.  All threads copy the segment list into LDS (one round trip to memory instead of one per
-// segment) and put it in order; thread 0 forms the groups; then one thread per tile writes the tile
-// records and one wave per gap fills the offset table of the tile it lies in, 64 rows at a time.
+// Barrier that orders LDS traffic only (lgkmcnt(0), then s_barrier): the steps of the map exchange data
+// through LDS alone, and __syncthreads() would also wait for every global store to land.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xC07F);              // lgkmcnt(0); vmcnt and expcnt untouched
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+// exclusive prefix sums of three values per thread over the block; totals to every thread
+struct Int3 { int a, b, c; };
+__device__ __forceinline__ Int3 block_scan3(Int3 v, Int3* excl, int* wave_tot /* LDS [3][16] */) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    Int3 incl = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int ua = __shfl_up(incl.a, o, 64), ub = __shfl_up(incl.b, o, 64), uc = __shfl_up(incl.c, o, 64);
+        if (lane >= o) { incl.a += ua; incl.b += ub; incl.c += uc; }
+    }
+    lds_barrier();                                 // wave_tot may still be read from an earlier scan
+    if (lane == 63) { wave_tot[wave] = incl.a; wave_tot[16 + wave] = incl.b; wave_tot[32 + wave] = incl.c; }
+    lds_barrier();
+    Int3 before = {0, 0, 0}, total = {0, 0, 0};
+#pragma unroll
+    for (int wv = 0; wv < nw; ++wv) {
+        const int ta = wave_tot[wv], tb = wave_tot[16 + wv], tc = wave_tot[32 + wv];
+        if (wv < wave) { before.a += ta; before.b += tb; before.c += tc; }
+        total.a += ta; total.b += tb; total.c += tc;
+    }
+    excl->a = before.a + incl.a - v.a; excl->b = before.b + incl.b - v.b; excl->c = before.c + incl.c - v.c;
+    return total;
+}
+
+// One block, a thread per segment.  The segment list is read into LDS in one round trip; the stable order
+// by expert comes from wave ballots (segments of the same expert inside a wave) plus a scan over the 16
+// waves; groups, positions inside the groups and the tiles of the groups come from two block-wide prefix
+// sums; then one thread per tile writes the tile records and the items fill the offset tables.
 __global__ __launch_bounds__(kMapThreads) void tilemap_kernel(const int32_t* __restrict__ seg_offset,
                                                               const int32_t* __restrict__ seg_expert, int nseg, int R,
                                                               int BM, int n_local, int gather, int max_tiles, TileMap m) {
     __shared__ SegWork w;
-    const int tid = threadIdx.x;
-    for (int i = tid; i <= nseg; i += kMapThreads) {
+    __shared__ int wave_cnt[kMapThreads / 64][MOE_MAX_LOCAL];
+    __shared__ int wave_tot[3 * 16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nth = blockDim.x, nw = nth >> 6;       // at least as many threads as segments (the launch sees to that)
+    for (int i = tid; i <= nseg; i += nth) {
         w.raw_off[i] = seg_offset[i];
         if (i < nseg) w.raw_exp[i] = seg_expert[i];
     }
-    __syncthreads();
-    tilemap_clean(w, nseg, R, n_local, tid, kMapThreads);
-    __syncthreads();
+    for (int i = tid; i < (kMapThreads / 64) * MOE_MAX_LOCAL; i += nth) (&wave_cnt[0][0])[i] = 0;
+    lds_barrier();
+    tilemap_clean(w, nseg, R, n_local, tid, nth);
+    lds_barrier();
     if (gather) {
-        tilemap_rank(w, nseg, tid, kMapThreads);
-        __syncthreads();
-        if (tid == 0) tilemap_starts(w, n_local);
-        __syncthreads();
-        tilemap_place(w, nseg, R, tid, kMapThreads);
-        __syncthreads();
+        // rank among the segments of the same expert: inside the wave from ballots over the bits of the expert id
+        const int e = tid < nseg ? w.raw_exp[tid] : -1;
+        unsigned long long peers = __ballot(e >= 0);
+#pragma unroll
+        for (int b = 0; b < 6; ++b) {                // MOE_MAX_LOCAL = 64 experts: six bits
+            const unsigned long long mb = __ballot((e >> b) & 1);
+            peers &= ((e >> b) & 1) ? mb : ~mb;
+        }
+        const int rank_in_wave = __popcll(peers & ((1ull << lane) - 1ull));
+        if (e >= 0 && rank_in_wave == 0) wave_cnt[wave][e] = __popcll(peers);
+        lds_barrier();
+        if (tid < n_local) {                         // exclusive scan over the waves, total per expert
+            int run = 0;
+#pragma unroll
+            for (int wv = 0; wv < nw; ++wv) {
+                const int c = wave_cnt[wv][tid];
+                wave_cnt[wv][tid] = run;
+                run += c;
+            }
+            w.cnt[tid] = run;
+        }
+        lds_barrier();
+        if (e >= 0) w.v0[tid] = wave_cnt[wave][e] + rank_in_wave;
+        if (wave == 0) {                             // where the items of every expert start
+            const int c = lane < n_local ? w.cnt[lane] : 0;
+            int incl = c;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int up = __shfl_up(incl, o, 64);
+                if (lane >= o) incl += up;
+            }
+            if (lane < n_local) w.pos[lane] = incl - c;
+            if (lane == 63) w.n_items = incl;
+        }
+        lds_barrier();
+        tilemap_place(w, nseg, R, tid, nth);
+    } else if (tid == 0) {
+        tilemap_merge(w, nseg, R);
     }
-    if (tid == 0) {
-        if (!gather) tilemap_merge(w, nseg, R);
-        tilemap_groups(w, BM, gather != 0, max_tiles);
-        *m.n_tiles = w.n_tiles;
+    lds_barrier();
+    // groups: item tid opens one or not; prefix sums give the group of every item, the rows in front of it
+    // and the gaps up to it
+    const int ni = w.n_items;
+    const bool live = tid < ni;
+    const bool opens = live && tilemap_opens(w, tid, gather != 0);
+    const bool gap = live && tilemap_gap(w, tid, gather != 0);
+    const int len = live ? w.hi[tid] - w.lo[tid] : 0;
+    Int3 ex;
+    const Int3 tot = block_scan3(Int3{opens ? 1 : 0, len, gap ? 1 : 0}, &ex, wave_tot);
+    const int ng = tot.a;
+    int* rows_before = w.raw_off;                    // rows in front of each group (the raw list is no longer needed)
+    if (live) {
+        w.grp[tid] = ex.a + (opens ? 1 : 0) - 1;
+        w.gaps[tid] = ex.c + (gap ? 1 : 0);
+        if (opens) { w.g_first[ex.a] = tid; rows_before[ex.a] = ex.b; }
     }
-    __syncthreads();
-    const int nt = w.n_tiles;
-    for (int t = tid; t < nt; t += kMapThreads) tilemap_tile(w, t, BM, m);
+    if (tid == 0) { w.g_first[ng] = ni; rows_before[ng] = tot.b; w.n_groups = ng; }
+    lds_barrier();
+    if (live) w.v0[tid] = ex.b - rows_before[w.grp[tid]];
+    const int g_rows = tid < ng ? rows_before[tid + 1] - rows_before[tid] : 0;
+    Int3 ex2;
+    const Int3 tot2 = block_scan3(Int3{tid < ng ? (g_rows + BM - 1) / BM : 0, 0, 0}, &ex2, wave_tot);
+    if (tid < ng) { w.g_rows[tid] = g_rows; w.g_tile0[tid] = ex2.a; }
+    // a well-formed list (non-decreasing offsets) stays below the bound; overlapping segments are cut off here
+    const int nt = tot2.a < max_tiles ? tot2.a : max_tiles;
+    if (tid == 0) { w.g_tile0[ng] = tot2.a; w.n_tiles = nt; *m.n_tiles = nt; }
+    lds_barrier();
+    for (int t = tid; t < nt; t += nth) tilemap_tile(w, t, BM, m);
     if (!gather) return;
-    const int lane = tid & 63, wave = tid >> 6;
-    for (int k = wave; k < w.n_items; k += kMapThreads / 64) {
-        RelJob job;
-        if (!tilemap_rel_job(w, k, BM, &job) || job.tile >= nt) continue;
-        for (int r = lane; r < job.v_hi - job.v_lo; r += 64)
-            m.rel[(size_t)job.tile * kRelPitch + r] = tilemap_rel(w, job, r);
+    // offset tables: every item works out its (at most two) runs of table entries; the runs are then parked
+    // in LDS, over the item arrays that nobody needs any more, and written by whole waves, 64 entries a time
+    RelJob job[2];
+    job[0].cnt = job[1].cnt = 0;
+    if (live) tilemap_rel_jobs(w, tid, BM, nt, job);
+    lds_barrier();
+    static_assert(offsetof(SegWork, gaps) == 5 * kMaxSeg * sizeof(int), "the six item arrays must be contiguous");
+    int* jd = &w.lo[0];                              // [2 * kMaxSeg] each
+    int* jc = jd + 2 * kMaxSeg;
+    int* jv = jc + 2 * kMaxSeg;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        jd[2 * tid + pass] = job[pass].dst;
+        jc[2 * tid + pass] = job[pass].cnt;
+        jv[2 * tid + pass] = job[pass].val;
+    }
+    lds_barrier();
+    // the runs go round the waves (run j to wave j % nw) so that a short list still uses all of them; lane l of
+    // wave w holds runs w + nw * l and w + nw * (64 + l), and the wave walks through them one at a time
+    int d_reg[2], c_reg[2], v_reg[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int j = wave + nw * (64 * h + lane);
+        d_reg[h] = jd[j];
+        c_reg[h] = jc[j];
+        v_reg[h] = jv[j];
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        unsigned long long todo = __ballot(c_reg[h] > 0);
+        while (todo) {
+            const int src = __builtin_ctzll(todo);
+            todo &= todo - 1;
+            const int dst = __builtin_amdgcn_readlane(d_reg[h], src), cnt = __builtin_amdgcn_readlane(c_reg[h], src);
+            const int val = __builtin_amdgcn_readlane(v_reg[h], src);
+            for (int r = lane; r < cnt; r += 64) m.rel[(size_t)dst + r] = val + r;
+        }
     }
 }
 
@@ -889,29 +1020,31 @@ extern "C" int moe_selfcheck_tile_map(const int32_t* seg_offset, const int32_t* 
     const int nth = 7;                                    // any thread count and order must give the same map
     for (int t = 0; t < nth; ++t) tilemap_clean(w, nseg, R, n_local, t, nth);
     if (gather) {
-        for (int t = nth - 1; t >= 0; --t) tilemap_rank(w, nseg, t, nth);
-        tilemap_starts(w, n_local);
-        for (int t = 0; t < nth; ++t) tilemap_place(w, nseg, R, t, nth);
+        tilemap_rank_host(w, nseg);
+        tilemap_starts_host(w, n_local);
+        for (int t = nth - 1; t >= 0; --t) tilemap_place(w, nseg, R, t, nth);
     } else {
         tilemap_merge(w, nseg, R);
     }
+    tilemap_groups_host(w, bm, gather != 0);
     const int max_tiles = (R + bm - 1) / bm + nseg;
-    tilemap_groups(w, bm, gather != 0, max_tiles + 1);
     const int nt = w.n_tiles;
     if (nt > max_tiles) return moe_set_error(MOE_EINTERNAL, "%d tiles exceed the bound %d", nt, max_tiles);
     std::vector<int32_t> row0(nt), nrows(nt), expert(nt), gat(nt), rel((size_t)nt * kRelPitch, -1);
     int32_t n_tiles = nt;
     TileMap m{&n_tiles, row0.data(), nrows.data(), expert.data(), gat.data(), rel.data()};
     for (int t = nt - 1; t >= 0; --t) tilemap_tile(w, t, bm, m);
-    std::vector<int> filled(nt, 0);
-    for (int k = 0; k < w.n_items; ++k) {
-        RelJob job;
-        if (!tilemap_rel_job(w, k, bm, &job)) continue;
-        if (job.tile < 0 || job.tile >= nt) return moe_set_error(MOE_EINTERNAL, "offset table for tile %d of %d", job.tile, nt);
-        if (job.row0 != row0[job.tile] || job.v_hi - job.v_lo != nrows[job.tile]) return moe_set_error(MOE_EINTERNAL, "tile %d: table and record disagree", job.tile);
-        ++filled[job.tile];
-        for (int r = 0; r < job.v_hi - job.v_lo; ++r) rel[(size_t)job.tile * kRelPitch + r] = tilemap_rel(w, job, r);
-    }
+    if (gather)
+        for (int k = 0; k < w.n_items; ++k) {
+            RelJob job[2];
+            tilemap_rel_jobs(w, k, bm, nt, job);
+            for (int pass = 0; pass < 2; ++pass)
+                for (int r = 0; r < job[pass].cnt; ++r) {
+                    int32_t& slot = rel[(size_t)job[pass].dst + r];
+                    if (slot != -1) return moe_set_error(MOE_EINTERNAL, "offset table entry %d written twice", job[pass].dst + r);
+                    slot = job[pass].val + r;
+                }
+        }
     std::vector<int> owner((size_t)R, -1);
     for (int i = 0; i < nseg; ++i) {
         const int lo = std::max(seg_offset[i], 0), hi = std::min(seg_offset[i + 1], R);
@@ -922,11 +1055,11 @@ extern "C" int moe_selfcheck_tile_map(const int32_t* seg_offset, const int32_t* 
     for (int t = 0; t < nt; ++t) {
         if (nrows[t] < 1 || nrows[t] > bm) return moe_set_error(MOE_EINTERNAL, "tile %d has %d rows", t, nrows[t]);
         if (gat[t] && !gather) return moe_set_error(MOE_EINTERNAL, "tile %d is gathered but gathering is off", t);
-        if (filled[t] != (gat[t] ? 1 : 0)) return moe_set_error(MOE_EINTERNAL, "tile %d: gather flag %d, table filled %d times", t, gat[t], filled[t]);
         int prev = -1;
         bool gaps = false;
         for (int r = 0; r < nrows[t]; ++r) {
             const int off = gat[t] ? rel[(size_t)t * kRelPitch + r] : r;
+            if (!gat[t] && rel[(size_t)t * kRelPitch + r] != -1) return moe_set_error(MOE_EINTERNAL, "tile %d has no gaps but an offset table", t);
             const int row = row0[t] + off;
             if (off < 0 || row < 0 || row >= R) return moe_set_error(MOE_EINTERNAL, "tile %d row %d maps to %d", t, r, row);
             if (r == 0 && off != 0) return moe_set_error(MOE_EINTERNAL, "tile %d does not start at its first row", t);
@@ -991,7 +1124,7 @@ static int ffn_impl(const void* recv, int32_t R, const int32_t* seg_offset, cons
     if (ev) MOE_HIP(hipEventRecord(ev[0], st));
     // gathered tiles address their rows by 32-bit byte offsets from the tile's first row
     const int gather = (dtype == MOE_BF16 && (size_t)R * (size_t)std::max(H, F) * 2 <= 0xFFFFFFFFull) ? 1 : 0;
-    hipLaunchKernelGGL(tilemap_kernel, dim3(1), dim3(kMapThreads), 0, st, seg_offset, seg_expert, nseg, R, bm, n_local, gather,
+        hipLaunchKernelGGL(tilemap_kernel, dim3(1), dim3(kMapThreads), 0, st, seg_offset, seg_expert, nseg, R, bm, n_local, gather,
                        (R + bm - 1) / bm + nseg, m);
     MOE_LAUNCH_CHECK("tilemap_kernel");
     if (ev) MOE_HIP(hipEventRecord(ev[1], st));

@@ -285,6 +285,8 @@ FFN_CASES = [
     ("bf16", 1, 2000, 256, 512, 4, 64),
     ("bf16", 2, 1500, 384, 256, 3, 200),
     ("bf16", 0, 900, 2048, 2304, 2, 31),                   # with pieces along K as well
+    ("bf16", 2, 3000, 256, 256, 64, 1024),                 # the limits: 64 local experts, 1024 segments (many of them empty)
+    ("bf16", 1, 5000, 128, 256, 32, 300),
 ]
 
 
