@@ -413,17 +413,29 @@ __global__ __launch_bounds__(kLayoutThreads) void chunk_layout_kernel(ChunkTable
                                                                       int32_t* __restrict__ piece_expert,
                                                                       int32_t* __restrict__ n_pieces) {
     __shared__ int kept[MOE_MAX_E], first[MOE_MAX_E], dest_cnt[MOE_MAX_G], wave_tot[kLayoutThreads / 64];
+    __shared__ int d_exp[MOE_MAX_E], d_beg[MOE_MAX_G + 1];    // the experts of every destination, ascending: d_exp[d_beg[d] .. d_beg[d+1])
     const int tid = threadIdx.x;
     if (tid < E) {
         const int c = raw_count[tid];
         kept[tid] = (capacity > 0 && c > capacity) ? capacity : c;
     }
+    if (tid < G) {
+        int n = 0;
+        for (int e = 0; e < E; ++e) n += (map.expert_gpu[e] == tid) ? 1 : 0;
+        dest_cnt[tid] = n;                                    // for now: experts of the destination
+    }
     __syncthreads();
-    if (tid < G) {                                            // thread d walks the experts of destination d in id order
+    if (tid == 0) {
         int run = 0;
+        for (int d = 0; d < G; ++d) { d_beg[d] = run; run += dest_cnt[d]; }
+        d_beg[G] = run;
+    }
+    __syncthreads();
+    if (tid < G) {                                            // thread d lists the experts of destination d in id order
+        int at = d_beg[tid], run = 0;
         for (int e = 0; e < E; ++e)
-            if (map.expert_gpu[e] == tid) { first[e] = run; run += kept[e]; }
-        dest_cnt[tid] = run;
+            if (map.expert_gpu[e] == tid) { d_exp[at++] = e; first[e] = run; run += kept[e]; }
+        dest_cnt[tid] = run;                                  // from here on: kept slots of the destination
     }
     __syncthreads();
     if (tid < E) tb.expert_first[tid] = first[tid];
@@ -440,8 +452,10 @@ __global__ __launch_bounds__(kLayoutThreads) void chunk_layout_kernel(ChunkTable
                 const int lo = min(tb.c_cumlo[c], dest_cnt[d]), hi = min(tb.c_cumhi[c], dest_cnt[d]);
                 size[u] = hi - lo;
                 if (hi > lo)
-                    for (int e = 0; e < E; ++e)               // experts of d whose slots meet [lo, hi)
-                        if (map.expert_gpu[e] == d && kept[e] > 0 && first[e] < hi && first[e] + kept[e] > lo) ++pieces[u];
+                    for (int i = d_beg[d]; i < d_beg[d + 1]; ++i) {   // experts of d whose slots meet [lo, hi)
+                        const int e = d_exp[i];
+                        if (kept[e] > 0 && first[e] < hi && first[e] + kept[e] > lo) ++pieces[u];
+                    }
             }
         }
         sum += size[u];
@@ -459,12 +473,14 @@ __global__ __launch_bounds__(kLayoutThreads) void chunk_layout_kernel(ChunkTable
             if (size[u] > 0) {
                 const int d = tb.c_dest[c];
                 const int lo = min(tb.c_cumlo[c], dest_cnt[d]), hi = lo + size[u];
-                for (int e = 0; e < E; ++e)
-                    if (map.expert_gpu[e] == d && kept[e] > 0 && first[e] < hi && first[e] + kept[e] > lo) {
+                for (int i = d_beg[d]; i < d_beg[d + 1]; ++i) {
+                    const int e = d_exp[i];
+                    if (kept[e] > 0 && first[e] < hi && first[e] + kept[e] > lo) {
                         piece_offset[piece0] = row0 + max(first[e], lo) - lo;
                         piece_expert[piece0] = e;
                         ++piece0;
                     }
+                }
             }
             row0 += size[u];
         }
