@@ -316,6 +316,29 @@ def test_expert_ffn_leaves_rows_outside_segments_untouched(H):
     assert H.rel_err(got[10:300], ref) < TOL["bf16"]
 
 
+def test_expert_ffn_rows_beyond_the_32_bit_offsets_of_a_gathered_tile(H):
+    """R * F * 2 bytes above 4 GiB: tiles may no longer gather rows from distant segments (their row offsets
+    are 32-bit byte offsets), so only adjacent segments of an expert share tiles.  Sampled rows against the
+    oracle, plus: no row outside the segments is written."""
+    Hd, F, R, n_local = 128, 16384, 140000, 2
+    assert R * F * 2 > 2 ** 32
+    cfg = small("c2_mixtral", H=Hd, F=F)
+    r = np.random.default_rng(99)
+    recv = W.round_to_dtype(r.standard_normal((R, Hd)).astype(np.float32), "bf16")
+    experts = [W.make_expert_weights(cfg, e) for e in range(n_local)]
+    off = [0, 300, 300, 20000, 20100, 60000, 60001, 99000, 99000, 120000, 139000]     # the last 1000 rows: no segment
+    exp = [0, 1, 1, 0, 1, 0, 1, 1, 0, 0]
+    out = H.run_ffn(H.dev(recv, "bf16"), off, exp, [H.weights_to_dev(w, "bf16") for w in experts], Hd, F, 2, "bf16")
+    assert torch.isnan(out[139000:]).all().item() and torch.isfinite(out[:139000]).all().item()
+    rows = np.unique(np.concatenate([r.integers(0, 139000, size=150), np.array(off[:-1]), np.array(off[1:]) - 1]))
+    rows = rows[(rows >= 0) & (rows < 139000)]
+    seg = np.searchsorted(np.array(off), rows, side="right") - 1
+    got = H.host(out[torch.from_numpy(rows).to(H.DEV)])
+    ref = np.stack([O.ffn(recv[i:i + 1], experts[exp[g]]["w1"], experts[exp[g]]["w_up"], experts[exp[g]]["w_down"], 2)[0]
+                    for i, g in zip(rows, seg)])
+    assert H.rel_err(got, ref) < TOL["bf16"]
+
+
 COMBINE_CASES = [W.get_config("c1_tiny_fp32"), small("c2_mixtral", T=333, H=520), small("c3_switch", T=1000, H=64),
                  small("c5_finegrained", T=257, H=264)]
 
