@@ -33,6 +33,18 @@ struct SegMap {                       // built on the host from expert_to_gpu an
 
 constexpr int kChunks = MOE_SLOTS_PER_BLOCK / 64;   // 16 chunks of 64 slots per block, in slot order
 
+// Lanes of the wave whose expert equals this lane's (0 <= e < 256; garbage for e < 0): the lanes that agree
+// on every bit of e.
+__device__ __forceinline__ unsigned long long same_expert_lanes(int e) {
+    unsigned long long peers = __ballot(e >= 0);
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {                     // MOE_MAX_E = 256 experts: eight bits
+        const unsigned long long mb = __ballot((e >> b) & 1);
+        peers &= ((e >> b) & 1) ? mb : ~mb;
+    }
+    return peers;
+}
+
 // cnt[chunk][e] for this block's 16 chunks; lane_rank[r] = rank of this lane's slot inside its
 // chunk among the lanes with the same expert.
 template <bool WANT_RANK>
@@ -47,13 +59,28 @@ __device__ __forceinline__ void block_chunk_counts(const int32_t* __restrict__ i
         lane_rank[r] = 0;
     }
     const unsigned long long lt = (1ull << lane) - 1ull;
-    for (int e = 0; e < E; ++e) {
+    if (E <= 16) {
+        for (int e = 0; e < E; ++e) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const unsigned long long m = __ballot(my_e[r] == e);
-            if (WANT_RANK && my_e[r] == e) lane_rank[r] = __popcll(m & lt);
-            if (lane == 0) cnt[(wave * 4 + r) * E + e] = __popcll(m);
+            for (int r = 0; r < 4; ++r) {
+                const unsigned long long m = __ballot(my_e[r] == e);
+                if (WANT_RANK && my_e[r] == e) lane_rank[r] = __popcll(m & lt);
+                if (lane == 0) cnt[(wave * 4 + r) * E + e] = __popcll(m);
+            }
         }
+        return;
+    }
+    // many experts: nine ballots per round instead of one per expert; the first lane of every group of equal
+    // experts writes the group's size, so the table starts from zero
+    for (int i = threadIdx.x; i < kChunks * E; i += 256) cnt[i] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int e = (my_e[r] >= 0 && my_e[r] < E) ? my_e[r] : -1;
+        const unsigned long long peers = same_expert_lanes(e);
+        const int rk = __popcll(peers & lt);
+        if (WANT_RANK) lane_rank[r] = rk;
+        if (e >= 0 && rk == 0) cnt[(wave * 4 + r) * E + e] = __popcll(peers);
     }
 }
 
@@ -104,10 +131,15 @@ __global__ __launch_bounds__(256) void scan_kernel(int32_t* __restrict__ block_h
     const int e = threadIdx.x;
     if (e < E) {
         int run = 0;
-        for (int b = 0; b < n_blocks; ++b) {
-            const int c = block_hist[(size_t)b * E + e];
-            block_hist[(size_t)b * E + e] = run;
-            run += c;
+        for (int b0 = 0; b0 < n_blocks; b0 += 32) {           // 32 loads in flight per round trip to memory
+            int c[32];
+#pragma unroll
+            for (int u = 0; u < 32; ++u) c[u] = (b0 + u < n_blocks) ? block_hist[(size_t)(b0 + u) * E + e] : 0;
+#pragma unroll
+            for (int u = 0; u < 32; ++u) {
+                if (b0 + u < n_blocks) block_hist[(size_t)(b0 + u) * E + e] = run;
+                run += c[u];
+            }
         }
         raw[e] = run;
         raw_count[e] = run;
@@ -149,9 +181,9 @@ constexpr int kSmallMaxSlots = 16384;
 constexpr int kSmallRounds = kSmallMaxSlots / (16 * 64);     // rounds of 64 slots per wave
 
 // The whole rank pass in one block of 1024 threads.  Wave w owns the slots [w*spw, (w+1)*spw),
-// round by round; per round the lanes are grouped by expert with ballots (one ballot per distinct
-// expert present) and the wave's running per-expert counts live in registers (lane e % 64 holds
-// expert e), so a round costs a few register operations per distinct expert.
+// round by round.  Few experts: one ballot per (expert, round), the running count is wave-uniform.
+// Many experts: ballots over the bits of the expert id give every lane the lanes of its round with
+// the same expert; the wave's running per-expert counts sit in LDS.
 __global__ __launch_bounds__(1024) void small_rank_kernel(const int32_t* __restrict__ idx, int n_slots, int E, int G,
                                                           int capacity, SegMap map, int32_t* __restrict__ raw_count,
                                                           int32_t* __restrict__ slot_rank,
@@ -172,7 +204,7 @@ __global__ __launch_bounds__(1024) void small_rank_kernel(const int32_t* __restr
         my_e[r] = (e < E) ? e : -1;                         // out of range: no rank
         my_rank[r] = -1;
     }
-    int run[MOE_MAX_E / 64] = {0, 0, 0, 0};                // lane l: counts of experts l, l+64, l+128, l+192
+    int few_cnt = 0;                                       // few experts: lane e ends up with the wave's count of expert e
     if (E <= 16) {
         // few experts: one ballot per (expert, round); the running count is wave-uniform
         for (int e = 0; e < E; ++e) {
@@ -185,34 +217,29 @@ __global__ __launch_bounds__(1024) void small_rank_kernel(const int32_t* __restr
                     cnt += __popcll(m);
                 }
             }
-            if (lane == e) run[0] = cnt;
+            if (lane == e) few_cnt = cnt;
         }
     } else {
+        // many experts: nine ballots per round give every lane the lanes with the same expert; the wave's
+        // running counts sit in its row of wave_cnt (only this wave touches it until the barrier below)
+        for (int i = lane; i < E; i += 64) wave_cnt[wave][i] = 0;
 #pragma unroll
         for (int r = 0; r < kSmallRounds; ++r) {
             if (r < rounds) {
                 const int e = my_e[r];
-                unsigned long long todo = __ballot(e >= 0);
-                while (todo) {                              // one trip per distinct expert in this round
-                    const int leader = __builtin_amdgcn_readfirstlane(__ffsll((long long)todo) - 1);
-                    const int cur = __builtin_amdgcn_readlane(e, leader);
-                    const unsigned long long m = __ballot(e == cur);
-                    const int slot = cur >> 6;              // wave-uniform
-                    const int holder = (slot == 0) ? run[0] : (slot == 1) ? run[1] : (slot == 2) ? run[2] : run[3];
-                    const int before = __builtin_amdgcn_readlane(holder, cur & 63);
-                    if (e == cur) my_rank[r] = before + __popcll(m & lt);
-                    if (lane == (cur & 63)) {
-                        const int add = __popcll(m);
-                        if (slot == 0) run[0] += add; else if (slot == 1) run[1] += add; else if (slot == 2) run[2] += add; else run[3] += add;
-                    }
-                    todo &= ~m;
+                const unsigned long long peers = same_expert_lanes(e);
+                const int rk = __popcll(peers & lt);
+                if (e >= 0) {
+                    const int before = wave_cnt[wave][e];
+                    my_rank[r] = before + rk;
+                    if (rk == 0) wave_cnt[wave][e] = before + __popcll(peers);
                 }
             }
         }
     }
-#pragma unroll
-    for (int i = 0; i < MOE_MAX_E / 64; ++i)
-        if (lane + 64 * i < E) wave_cnt[wave][lane + 64 * i] = run[i];
+    if (E <= 16) {
+        if (lane < E) wave_cnt[wave][lane] = few_cnt;
+    }
     __syncthreads();
     if (threadIdx.x < E) {                                 // exclusive scan over the 16 waves
         const int e = threadIdx.x;
