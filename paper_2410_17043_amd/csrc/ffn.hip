@@ -206,7 +206,7 @@ __host__ __device__ inline void tilemap_tile(const SegWork& w, int t, int BM, co
 // run of consecutive table entries with consecutive values: rel[dst + r] = val + r for r < cnt.
 struct RelJob { int dst, cnt, val; };
 __host__ __device__ inline void tilemap_rel_jobs(const SegWork& w, int k, int BM, int n_tiles, RelJob (&job)[2]) {
-    job[0].cnt = job[1].cnt = 0;
+    job[0] = job[1] = RelJob{0, 0, 0};
     const int g = w.grp[k], len = w.hi[k] - w.lo[k];
     const int q_a = w.v0[k] / BM, q_b = (w.v0[k] + len - 1) / BM;
     for (int pass = 0; pass < 2; ++pass) {
@@ -348,8 +348,7 @@ __global__ __launch_bounds__(kMapThreads) void tilemap_kernel(const int32_t* __r
     if (!gather) return;
     // offset tables: every item works out its (at most two) runs of table entries; the runs are then parked
     // in LDS, over the item arrays that nobody needs any more, and written by whole waves, 64 entries a time
-    RelJob job[2];
-    job[0].cnt = job[1].cnt = 0;
+    RelJob job[2] = {{0, 0, 0}, {0, 0, 0}};
     if (live) tilemap_rel_jobs(w, tid, BM, nt, job);
     lds_barrier();
     static_assert(offsetof(SegWork, gaps) == 5 * kMaxSeg * sizeof(int), "the six item arrays must be contiguous");
@@ -566,9 +565,11 @@ __device__ __forceinline__ float fast_silu(float a) {
     return a * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.44269504088896f * a));
 }
 // tanh-form GELU: 0.5 a (1 + tanh(u)) = a * sigmoid(2u), u = sqrt(2/pi) (a + 0.044715 a^3); one exp2 and one rcp
+// (the exponent -log2(e) * 2u = a * (k1 + k2 a^2) is formed with the constants folded: five plain operations around the two slow ones)
 __device__ __forceinline__ float fast_gelu(float a) {
-    const float u2 = 1.5957691216057308f * (a + 0.044715f * a * a * a);
-    return a * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.44269504088896f * u2));
+    const float k1 = -1.44269504088896f * 1.5957691216057308f, k2 = k1 * 0.044715f;
+    const float arg = a * __builtin_fmaf(k2, a * a, k1);
+    return a * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(arg));
 }
 template <int EPI> __device__ __forceinline__ float epilogue_bf16(float a, float b) {
     if (EPI == EPI_SILU) return fast_silu(a);
