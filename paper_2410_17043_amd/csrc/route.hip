@@ -104,7 +104,7 @@ __device__ __forceinline__ void select_topk(const double* __restrict__ z, int E,
 }
 
 template <int DT, int NT, int PF>
-__global__ __launch_bounds__(512) void route_mfma_kernel(const void* __restrict__ x, const void* __restrict__ wg,
+__global__ __launch_bounds__(NT == 1 ? 1024 : 512) void route_mfma_kernel(const void* __restrict__ x, const void* __restrict__ wg,
                                                           const float* __restrict__ bias, int T, int H, int E, int k,
                                                           int renorm, int32_t* __restrict__ topk_idx,
                                                           float* __restrict__ topk_w) {
@@ -198,8 +198,9 @@ int launch_route_mfma(const moe_ctx* c, const void* x, const void* wg, const flo
     const moe_shape& s = c->s;
     const int V = Chunk<DT>::V;
     const int blocks = (s.T + 15) / 16, ngrp = (s.H / V + 3) / 4;
-    int S = 1;                                            // waves per block: about 2048 waves in all, at most 8
-    while (S < 8 && blocks * S < 2048 && 2 * S <= ngrp) S *= 2;
+    int S = 1;                                            // waves per block: about 2048 waves in all (4096 with one expert tile), at most 8 (16)
+    const int s_max = (NT == 1) ? 16 : 8, waves = (NT == 1) ? 4096 : 2048;
+    while (S < s_max && blocks * S < waves && 2 * S <= ngrp) S *= 2;
     const size_t lds = ((size_t)16 * s.E + (size_t)S * 16 * NT * 16) * sizeof(double);   // at most 96 KB
     static bool attr_done = false;
     if (!attr_done) {
@@ -217,7 +218,7 @@ template <int DT>
 int route_dispatch(const moe_ctx* c, const void* x, const void* wg, const float* bias, int32_t* idx, float* w,
                    hipStream_t st) {
     const int E = c->s.E;
-    if (E <= 16) return launch_route_mfma<DT, 1, 8>(c, x, wg, bias, idx, w, st);
+    if (E <= 16) return launch_route_mfma<DT, 1, 4>(c, x, wg, bias, idx, w, st);
     if (E <= 32) return launch_route_mfma<DT, 2, 4>(c, x, wg, bias, idx, w, st);
     return launch_route_mfma<DT, 4, 3>(c, x, wg, bias, idx, w, st);   // E > 64: several passes of 64 experts
 }
