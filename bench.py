@@ -290,7 +290,7 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from Python instead of replaying a HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU's share of the layer; there is no multi-GPU path in this build "
+        print("bench.py measures one GPU's share of the layer; there is no multi-GPU path in this library "
               "(run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
 
