@@ -28,7 +28,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 GEMM1_TRAFFIC_BYTES = {"c2_mixtral": 3.9042e6 * 1024 * 2.0 + 6.6752e5 * 1024}
 
 
-def build_workload(cfg, torch, P, W):
+def build_workload(cfg, torch, P, W, share="bottleneck"):
     """Everything a step needs, resident on the GPU.  Returns a dict of tensors and the step closure."""
     dev = "cuda:0"
     tdt = P.TORCH_DTYPE[cfg.dtype]
@@ -38,7 +38,11 @@ def build_workload(cfg, torch, P, W):
 
     traffic = W.make_traffic_matrix(cfg)
     D = traffic["D"].copy()
-    g = int(np.argmax(D.sum(axis=0)))                       # the GPU that receives most sets the layer time
+    received = D.sum(axis=0)
+    if share == "median":
+        g = int(np.argsort(received, kind="stable")[len(received) // 2])
+    else:
+        g = int(np.argmax(received))                        # the GPU that receives most sets the layer time
     inp = W.make_layer_inputs(cfg, g)
     e2g = inp["expert_to_gpu"]
     local = [e for e in range(cfg.E) if e2g[e] == g]
@@ -286,6 +290,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c2_mixtral")
+    ap.add_argument("--share", choices=["bottleneck", "median"], default="bottleneck",
+                    help="which GPU's share to run: the one that receives most rows (sets the layer time) or the median one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="launch every kernel from Python instead of replaying a HIP graph")
     args = ap.parse_args()
@@ -303,7 +309,7 @@ def main():
         print("bench.py needs the MI355X (no CPU fallback exists)", file=sys.stderr)
         sys.exit(2)
     cfg = W.get_config(args.workload)
-    wl = build_workload(cfg, torch, P, W)
+    wl = build_workload(cfg, torch, P, W, args.share)
     step = wl["step"]
 
     # The step is recorded once into a HIP graph (no memset nodes: the library clears nothing with
@@ -357,7 +363,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "T": T, "H": H, "F": F, "E": cfg.E, "k": k, "G": cfg.G,
-                   "received_rows": R, "gpu_under_test": wl["g"], "act": cfg.act},
+                   "received_rows": R, "gpu_under_test": wl["g"], "share": args.share, "act": cfg.act},
         "wall_ms_per_step": wall_ms, "launch": "hip graph replay" if use_graph else "eager",
         "stage_ms": {n: round(v, 4) for n, v in stage_ms.items()},
         "stage_rate": {
@@ -371,7 +377,7 @@ def main():
         },
         "roofline": {"kernel": "gemm_bf16_kernel<SwiGLU> (first FFN GEMM with the activation)", "bound": "mfma",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": GEMM1_TRAFFIC_BYTES.get(cfg.name),
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": GEMM1_TRAFFIC_BYTES.get(cfg.name) if args.share == "bottleneck" else None,
                      "launch_ms": float(gemm_ms[1]), "flops_per_launch": flops_gemm1},
     }
     line["paper_model"] = paper_model(cfg, wl, stage_ms, P)
