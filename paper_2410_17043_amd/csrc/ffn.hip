@@ -431,13 +431,15 @@ __host__ __device__ __forceinline__ void tile_of_block_bands(int id, int tiles_m
     *tm = 8 * q + v % lm;
     *tn = v / lm;
 }
-// With fewer than 16 M-tiles a band is a single row of tiles (33 operand tiles for the 32 resident blocks
-// instead of 12); when the N side has thicker bands the same numbering is used with the roles of M and N
-// exchanged: XCD x owns a band of N-tiles and all XCDs sweep the M-tiles in step.  Measured at 2000 rows
-// of the 4096 -> 14336 -> 4096 shape: +7 % on both GEMMs; bands of two rows (17 M-tiles) gain nothing.
+// With fewer than 32 M-tiles a band is at most three rows of tiles (patches of 1 x 32 or 2 x 16 tiles: 33 or
+// 18 operand tiles for the 32 resident blocks instead of 12); when the N side has thicker bands the same
+// numbering is used with the roles of M and N exchanged: XCD x owns a band of N-tiles and all XCDs sweep
+// the M-tiles in step.  Measured at the 4096 -> 14336 -> 4096 shape: +7 % on both GEMMs at 2000 rows (bands
+// of one row), +2.5 % at 6745 and 7900 rows (three rows), +1 % at 4147 and 5000 (two rows); with bands of
+// four to seven rows the exchange gains or loses less than 1 %, so those keep the M bands.
 __host__ __device__ __forceinline__ void tile_of_block(int id, int total, int tiles_m, int tiles_n, int* tm, int* tn) {
     (void)total;
-    if (tiles_m / 8 < 2 && tiles_n / 8 > tiles_m / 8) tile_of_block_bands(id, tiles_n, tiles_m, tn, tm);
+    if (tiles_m / 8 < 4 && tiles_n / 8 > tiles_m / 8) tile_of_block_bands(id, tiles_n, tiles_m, tn, tm);
     else tile_of_block_bands(id, tiles_m, tiles_n, tm, tn);
 }
 
