@@ -25,7 +25,7 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM-side bytes per launch of the first FFN GEMM at c2_mixtral from rocprofv3 counters (FETCH_SIZE x 2.0 +
 # WRITE_SIZE x 1.0, see profiles/bench_c2_mixtral_layer_share.md); None once the kernel has changed since.
-GEMM1_TRAFFIC_BYTES = {"c2_mixtral": 3.9042e6 * 1024 * 2.0 + 6.6752e5 * 1024}
+GEMM1_TRAFFIC_BYTES = {"c2_mixtral": 3.9033e6 * 1024 * 2.0 + 6.6752e5 * 1024}
 
 
 def build_workload(cfg, torch, P, W, share="bottleneck"):
