@@ -12,11 +12,21 @@ rate B_i in each direction.
 Pins (tests/test_oracle_schedule.py): the three-GPU example of the network figure
 (3 time units for the naive order, 2 for the reordered one, b_max = 2), the
 closed form against brute force over every per-source order for n <= 4, padding
-and round invariants, homogeneous reduction of the heterogeneous bound.
+and round invariants, homogeneous reduction of the heterogeneous bound, hand
+arithmetic for the per-port bound.
 
-Parity unpinned: `alg1_order`.  Algorithm 1 does not say how tokens are arranged
-"to avoid conflicts"; the rule used here is a stated reading.  What is pinned
-about it is validity (complete, contention-free, makespan >= b_max).
+`alg1_order`: Algorithm 1 does not say how tokens are arranged "to avoid
+conflicts"; the rule used here is a stated reading.  Pinned about it: what the
+text in front of the algorithm fixes (transmission at the bottleneck GPU runs
+without a gap from time 0 for exactly b_max), validity (complete,
+contention-free), two cases worked by hand that exercise the sort direction
+and every tie-break, and its distance from the brute-force optimum on stored
+seeded matrices (tests/golden/order_ratios.txt).  What no pin can decide is
+whether the authors' own implementation breaks ties the same way: the paper
+does not say.
+
+`send_order` is what the library hands to the send buffer: the best of three
+whole-flow orders under `simulate`, improved by adjacent exchanges.
 """
 from __future__ import annotations
 
@@ -279,3 +289,114 @@ def alg1_order(D, B=None):
         dest_order.append(real + empty + [i])
     ends = [hi for tl in send_busy for _, hi in tl]
     return {"start": start, "dest_order": dest_order, "makespan": max([Fraction(0)] + ends)}
+
+
+def rounds_order(D, B=None):
+    """Whole-flow order read off the rounds of Appendix A: GPU i serves its destinations
+    in the order in which they first appear in its rounds (empty ones, then i itself, last)."""
+    sched, _ = rounds(D, B)
+    n = len(D)
+    out = []
+    for i in range(n):
+        first = {}
+        for r, (dst, _tau, _real) in enumerate(sched):
+            if dst[i] >= 0:
+                first.setdefault(dst[i], r)
+        real = sorted(first, key=lambda j: (first[j], j))
+        out.append(real + [j for j in range(n) if j != i and j not in first] + [i])
+    return out
+
+
+def list_order(D, B=None):
+    """Whole-flow order built while the transfer is played forward on the big switch
+    (Sec. 2.4) under the sharing rule of `simulate`: whenever a GPU has nothing in
+    flight it starts, among the flows it still has to send, the one whose receiver
+    has the fewest flows coming in at that moment (a free port if there is one:
+    Theorem 2 asks for no contention at the receiving side), then the largest flow,
+    then the lowest destination.  GPUs that decide at the same instant do so by
+    descending amount still to send (scaled by their rate), lowest index first,
+    and see the choices made before theirs.  Returns (order, completion time); the
+    time is by construction what `simulate` gives for the order.
+    """
+    n = len(D)
+    Bf = [Fraction(1)] * n if B is None else [Fraction(b) for b in B]
+    todo = [{j: Fraction(int(D[i][j])) for j in range(n) if j != i and int(D[i][j]) > 0} for i in range(n)]
+    cur = [None] * n                                         # [dst, tokens left] of the flow in flight
+    order = [[] for _ in range(n)]
+    t = Fraction(0)
+    while True:
+        idle = [i for i in range(n) if cur[i] is None and todo[i]]
+        for i in sorted(idle, key=lambda i: (-sum(todo[i].values()) / Bf[i], i)):
+            fan_in = [0] * n
+            for c in cur:
+                if c is not None:
+                    fan_in[c[0]] += 1
+            j = min(todo[i], key=lambda j: (fan_in[j], -todo[i][j], j))
+            cur[i] = [j, todo[i].pop(j)]
+            order[i].append(j)
+        if all(c is None for c in cur):
+            break
+        fan_in = [0] * n
+        for c in cur:
+            if c is not None:
+                fan_in[c[0]] += 1
+        rate = [None if c is None else min(Bf[i], Bf[c[0]] / fan_in[c[0]]) for i, c in enumerate(cur)]
+        dt = min(c[1] / rate[i] for i, c in enumerate(cur) if c is not None)
+        t += dt
+        for i, c in enumerate(cur):
+            if c is not None:
+                c[1] -= rate[i] * dt
+                if c[1] == 0:
+                    cur[i] = None
+    full = [order[i] + [j for j in range(n) if j != i and j not in order[i]] + [i] for i in range(n)]
+    return full, t
+
+
+IMPROVE_MARGIN = Fraction(1, 10 ** 9)     # an exchange must gain more than this fraction of the time
+
+
+def improve_order(D, B, order, max_evals=None):
+    """Hill climbing on a whole-flow order: GPU by GPU, position by position, two
+    neighbouring non-empty flows of a GPU are exchanged and the exchange is kept
+    when `simulate` gets smaller by more than IMPROVE_MARGIN of its value; passes
+    repeat until one changes nothing or `max_evals` (default 64 n) exchanges were
+    tried.  Returns (order, time)."""
+    n = len(D)
+    order = [list(o) for o in order]
+    n_real = [sum(1 for j in order[i] if j != i and int(D[i][j]) > 0) for i in range(n)]
+    for i in range(n):                                       # non-empty flows first, their relative order kept
+        order[i] = ([j for j in order[i] if j != i and int(D[i][j]) > 0] +
+                    [j for j in order[i] if j != i and int(D[i][j]) <= 0] + [i])
+    best = simulate(D, B, order)
+    budget = 64 * n if max_evals is None else max_evals
+    changed = True
+    while changed and budget > 0:
+        changed = False
+        for i in range(n):
+            for p in range(n_real[i] - 1):
+                if budget <= 0:
+                    break
+                budget -= 1
+                order[i][p], order[i][p + 1] = order[i][p + 1], order[i][p]
+                v = simulate(D, B, order)
+                if v < best * (1 - IMPROVE_MARGIN):
+                    best, changed = v, True
+                else:
+                    order[i][p], order[i][p + 1] = order[i][p + 1], order[i][p]
+    return order, best
+
+
+def send_order(D, B=None, max_evals=None):
+    """The whole-flow order handed to the send buffer: the candidate with the smallest
+    `simulate` among Algorithm 1's order, the order read off the rounds and the
+    list order (the earlier candidate wins unless a later one is better by more
+    than IMPROVE_MARGIN), then `improve_order`.  Returns dict(dest_order, time,
+    source (0, 1, 2), candidate_times)."""
+    cands = [alg1_order(D, B)["dest_order"], rounds_order(D, B), list_order(D, B)[0]]
+    times = [simulate(D, B, c) for c in cands]
+    k = 0
+    for c in (1, 2):
+        if times[c] < times[k] * (1 - IMPROVE_MARGIN):
+            k = c
+    order, t = improve_order(D, B, cands[k], max_evals)
+    return {"dest_order": order, "time": t, "source": k, "candidate_times": times}
