@@ -217,13 +217,18 @@ typedef struct {
     int32_t n_rounds;
     double* duration;        /* [n_rounds] length of each round */
     int32_t* dst;            /* [n_rounds*n] receiver of GPU i in round r, -1 = idle */
-    int32_t* dest_order;     /* [n*n] row i: the order in which GPU i sends to all n destinations
-                                (real flows by planned start, then empty ones, then i itself) */
-    double* start;           /* [n*n] planned start of flow i->j in the per-destination order, -1 if empty */
+    int32_t* dest_order;     /* [n*n] row i: the order in which GPU i sends to all n destinations when whole
+                                flows go out back to back; the row to hand to moe_dispatch (non-empty flows,
+                                then empty ones, then i itself) */
+    int32_t* alg1_order;     /* [n*n] the same for Algorithm 1's plan: real flows by planned start */
+    double* start;           /* [n*n] Algorithm 1: planned start of flow i->j, -1 if empty */
     double bmax;             /* Theorem 2 / Theorem 4 lower bound */
     double port_bound;       /* looser bound max(sum_j d_ij/B_i, sum_i d_ij/B_j) */
     double makespan_rounds;  /* sum of round durations (== bmax up to rounding) */
-    double makespan_order;   /* end of the last flow in the per-destination plan */
+    double makespan_order;   /* Algorithm 1: end of the last flow in its plan (flows wait for their slot) */
+    double order_time;       /* aurora_simulate of dest_order */
+    double candidate_time[3];/* aurora_simulate of the three candidate orders (see below) */
+    int32_t order_source;    /* which candidate dest_order grew from: 0, 1 or 2 */
 } aurora_schedule;
 
 /* Transmission order of one all-to-all (Sec. 4.2 Theorem 2 and Algorithm 1;
@@ -232,10 +237,18 @@ typedef struct {
  *   B   HOST [n] link rates > 0, or NULL for all 1
  * Traffic is scaled to p_ij = d_ij / min(B_i,B_j).  `rounds` is the schedule of
  * Appendix A: the padded matrix is decomposed into permutations, in each round
- * every GPU sends to a distinct GPU; it attains bmax.  `dest_order` is a
- * non-preemptive per-destination order from a greedy reading of Algorithm 1
- * (bottleneck GPU first, then GPUs by remaining traffic, each flow placed in the
- * earliest gap free at both ends). */
+ * every GPU sends to a distinct GPU; it attains bmax (aurora_chunks turns it
+ * into a send plan).  `alg1_order`, `start`, `makespan_order` are a greedy
+ * reading of Algorithm 1 on whole flows: the bottleneck GPU's binding side back
+ * to back from time 0, then GPUs by remaining traffic, each flow placed in the
+ * earliest gap free at both ends.  A send buffer that holds whole flows is sent
+ * back to back, without the waits of that plan, so `dest_order` is chosen by
+ * what aurora_simulate gives: the best of (0) Algorithm 1's order, (1)
+ * destinations by their first round in the Appendix A schedule, (2) an order
+ * built while playing the transfer forward (an idle GPU starts the flow whose
+ * receiver has the fewest incoming flows, then the largest flow); then neighbouring
+ * flows of a GPU are exchanged while that shortens the simulated time (at most
+ * 64 n trials).  order_time >= port_bound always, >= bmax for equal rates. */
 int aurora_order(int32_t n, const int64_t* D, const double* B, aurora_schedule* out);
 void aurora_schedule_free(aurora_schedule* s);
 

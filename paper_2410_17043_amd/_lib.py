@@ -19,8 +19,10 @@ class moe_expert_w(C.Structure):
 class aurora_schedule(C.Structure):
     _fields_ = [("n", C.c_int32), ("n_rounds", C.c_int32), ("duration", C.POINTER(C.c_double)),
                 ("dst", C.POINTER(C.c_int32)), ("dest_order", C.POINTER(C.c_int32)),
+                ("alg1_order", C.POINTER(C.c_int32)),
                 ("start", C.POINTER(C.c_double)), ("bmax", C.c_double), ("port_bound", C.c_double),
-                ("makespan_rounds", C.c_double), ("makespan_order", C.c_double)]
+                ("makespan_rounds", C.c_double), ("makespan_order", C.c_double), ("order_time", C.c_double),
+                ("candidate_time", C.c_double * 3), ("order_source", C.c_int32)]
 
 
 class aurora_coloc_times(C.Structure):

@@ -257,9 +257,11 @@ def aurora_order(D, B=None):
             "duration": np.array([s.duration[r] for r in range(nr)], dtype=np.float64),
             "dst": np.array([s.dst[i] for i in range(nr * n)], dtype=np.int32).reshape(nr, n),
             "dest_order": np.array([s.dest_order[i] for i in range(n * n)], dtype=np.int32).reshape(n, n),
+            "alg1_order": np.array([s.alg1_order[i] for i in range(n * n)], dtype=np.int32).reshape(n, n),
             "start": np.array([s.start[i] for i in range(n * n)], dtype=np.float64).reshape(n, n),
             "bmax": s.bmax, "port_bound": s.port_bound, "makespan_rounds": s.makespan_rounds,
-            "makespan_order": s.makespan_order,
+            "makespan_order": s.makespan_order, "order_time": s.order_time,
+            "candidate_time": [s.candidate_time[c] for c in range(3)], "order_source": s.order_source,
         }
     finally:
         lib.aurora_schedule_free(C.byref(s))

@@ -236,6 +236,157 @@ void plan_order(const Mat& P, std::vector<int32_t>& dest_order, std::vector<doub
     *makespan = end;
 }
 
+// Completion time when GPU i sends to order[i*n ..] one destination after another on the big switch of
+// Sec. 2.4: a receiver with m incoming flows gives each B_recv / m, a flow runs at min(B_send, share).
+double simulate_order(int n, const int64_t* D, const double* B, const int32_t* order) {
+    std::vector<int> pos(n, 0), cur(n, -1), fan(n);
+    std::vector<double> left(n, 0.0), rate(n, 0.0);
+    auto next_flow = [&](int i) {
+        cur[i] = -1;
+        while (pos[i] < n) {
+            const int j = order[i * n + pos[i]++];
+            if (j != i && D[i * n + j] > 0) { cur[i] = j; left[i] = (double)D[i * n + j]; break; }
+        }
+    };
+    for (int i = 0; i < n; ++i) next_flow(i);
+    double t = 0.0;
+    for (;;) {
+        std::fill(fan.begin(), fan.end(), 0);
+        bool any = false;
+        for (int i = 0; i < n; ++i)
+            if (cur[i] >= 0) { ++fan[cur[i]]; any = true; }
+        if (!any) break;
+        double dt = -1.0;
+        for (int i = 0; i < n; ++i) {
+            if (cur[i] < 0) continue;
+            const double bs = B ? B[i] : 1.0, br = B ? B[cur[i]] : 1.0;
+            rate[i] = std::min(bs, br / fan[cur[i]]);
+            const double need = left[i] / rate[i];
+            dt = (dt < 0.0) ? need : std::min(dt, need);
+        }
+        t += dt;
+        for (int i = 0; i < n; ++i) {
+            if (cur[i] < 0) continue;
+            left[i] -= rate[i] * dt;
+            if (left[i] <= 1e-9 * (double)D[i * n + cur[i]]) next_flow(i);
+        }
+    }
+    return t;
+}
+
+// Row i of a whole-flow order: the given non-empty flows, then the empty destinations, then i itself.
+void fill_order_row(int n, int i, const std::vector<int>& real, int32_t* row) {
+    std::vector<char> used(n, 0);
+    int p = 0;
+    for (int j : real) { row[p++] = j; used[j] = 1; }
+    for (int j = 0; j < n; ++j)
+        if (j != i && !used[j]) row[p++] = j;
+    row[p] = i;
+}
+
+// Whole-flow order read off the rounds of Appendix A: destinations in the order of their first round.
+void order_from_rounds(int n, const std::vector<Round>& rounds, std::vector<int32_t>& order) {
+    order.assign((size_t)n * n, 0);
+    for (int i = 0; i < n; ++i) {
+        std::vector<int> real;
+        std::vector<char> seen(n, 0);
+        for (const Round& rd : rounds) {
+            const int j = rd.dst[i];
+            if (j >= 0 && !seen[j]) { seen[j] = 1; real.push_back(j); }
+        }
+        fill_order_row(n, i, real, &order[(size_t)i * n]);
+    }
+}
+
+// Whole-flow order built while the transfer is played forward under the sharing rule of simulate_order:
+// a GPU with nothing in flight starts the flow whose receiver has the fewest incoming flows at that moment
+// (a free port if there is one: no contention at the receiving side, Theorem 2), then the largest flow, then
+// the lowest destination; GPUs deciding at the same instant go by descending traffic left to send.
+void order_by_list(int n, const int64_t* D, const double* B, std::vector<int32_t>& order) {
+    std::vector<std::vector<int64_t>> todo(n, std::vector<int64_t>(n, 0));
+    for (int i = 0; i < n; ++i)
+        for (int j = 0; j < n; ++j)
+            if (i != j) todo[i][j] = D[i * n + j];
+    std::vector<std::vector<int>> seq(n);
+    std::vector<int> cur(n, -1), fan(n), idle;
+    std::vector<double> left(n, 0.0), rate(n, 0.0), to_send(n);
+    for (;;) {
+        idle.clear();
+        for (int i = 0; i < n; ++i) {
+            int64_t s = 0;
+            for (int j = 0; j < n; ++j) s += todo[i][j];
+            to_send[i] = (double)s / (B ? B[i] : 1.0);
+            if (cur[i] < 0 && s > 0) idle.push_back(i);
+        }
+        std::stable_sort(idle.begin(), idle.end(), [&](int a, int c) { return to_send[a] > to_send[c]; });
+        for (int i : idle) {
+            std::fill(fan.begin(), fan.end(), 0);
+            for (int s = 0; s < n; ++s)
+                if (cur[s] >= 0) ++fan[cur[s]];
+            int bj = -1;
+            for (int j = 0; j < n; ++j) {
+                if (todo[i][j] <= 0) continue;
+                if (bj < 0 || fan[j] < fan[bj] || (fan[j] == fan[bj] && todo[i][j] > todo[i][bj])) bj = j;
+            }
+            cur[i] = bj;
+            left[i] = (double)todo[i][bj];
+            todo[i][bj] = 0;
+            seq[i].push_back(bj);
+        }
+        std::fill(fan.begin(), fan.end(), 0);
+        bool any = false;
+        for (int i = 0; i < n; ++i)
+            if (cur[i] >= 0) { ++fan[cur[i]]; any = true; }
+        if (!any) break;
+        double dt = -1.0;
+        for (int i = 0; i < n; ++i) {
+            if (cur[i] < 0) continue;
+            rate[i] = std::min(B ? B[i] : 1.0, (B ? B[cur[i]] : 1.0) / fan[cur[i]]);
+            const double need = left[i] / rate[i];
+            dt = (dt < 0.0) ? need : std::min(dt, need);
+        }
+        for (int i = 0; i < n; ++i) {
+            if (cur[i] < 0) continue;
+            left[i] -= rate[i] * dt;
+            if (left[i] <= 1e-9 * (double)D[i * n + cur[i]]) cur[i] = -1;
+        }
+    }
+    order.assign((size_t)n * n, 0);
+    for (int i = 0; i < n; ++i) fill_order_row(n, i, seq[i], &order[(size_t)i * n]);
+}
+
+constexpr double kImproveMargin = 1e-9;      // an exchange must gain more than this fraction of the time
+
+// Hill climbing: two neighbouring non-empty flows of a GPU are exchanged and the exchange is kept when the
+// simulated completion time drops by more than kImproveMargin of its value; at most 64 n exchanges are tried.
+double improve_order(int n, const int64_t* D, const double* B, std::vector<int32_t>& order) {
+    std::vector<int> n_real(n, 0);
+    for (int i = 0; i < n; ++i) {
+        std::vector<int> real;
+        for (int p = 0; p < n; ++p) {
+            const int j = order[(size_t)i * n + p];
+            if (j != i && D[i * n + j] > 0) real.push_back(j);
+        }
+        n_real[i] = (int)real.size();
+        fill_order_row(n, i, real, &order[(size_t)i * n]);
+    }
+    double best = simulate_order(n, D, B, order.data());
+    int budget = 64 * n;
+    bool changed = true;
+    while (changed && budget > 0) {
+        changed = false;
+        for (int i = 0; i < n; ++i)
+            for (int p = 0; p + 1 < n_real[i] && budget > 0; ++p) {
+                --budget;
+                std::swap(order[(size_t)i * n + p], order[(size_t)i * n + p + 1]);
+                const double v = simulate_order(n, D, B, order.data());
+                if (v < best * (1.0 - kImproveMargin)) { best = v; changed = true; }
+                else std::swap(order[(size_t)i * n + p], order[(size_t)i * n + p + 1]);
+            }
+    }
+    return best;
+}
+
 // Hopcroft-Karp on the edges of weight <= limit; left side na, right side nb.
 struct HopcroftKarp {
     int na, nb;
@@ -288,6 +439,7 @@ extern "C" void aurora_schedule_free(aurora_schedule* s) {
     free(s->duration);
     free(s->dst);
     free(s->dest_order);
+    free(s->alg1_order);
     free(s->start);
     memset(s, 0, sizeof(*s));
 }
@@ -310,15 +462,29 @@ extern "C" int aurora_order(int32_t n, const int64_t* D, const double* B, aurora
         }
         out->port_bound = pb;
         const std::vector<Round> rounds = plan_rounds(P, out->bmax);
-        std::vector<int32_t> order;
+        std::vector<int32_t> order, by_rounds, by_list;
         std::vector<double> start;
         plan_order(P, order, start, &out->makespan_order);
+        // the order for the send buffer: the best of three whole-flow orders when run back to back (an earlier
+        // candidate stays unless a later one is better by more than the margin), then adjacent exchanges
+        order_from_rounds(n, rounds, by_rounds);
+        order_by_list(n, D, B, by_list);
+        const std::vector<int32_t>* cand[3] = {&order, &by_rounds, &by_list};
+        int pick = 0;
+        for (int c = 0; c < 3; ++c) {
+            out->candidate_time[c] = simulate_order(n, D, B, cand[c]->data());
+            if (c > 0 && out->candidate_time[c] < out->candidate_time[pick] * (1.0 - kImproveMargin)) pick = c;
+        }
+        std::vector<int32_t> chosen = *cand[pick];
+        out->order_source = pick;
+        out->order_time = improve_order(n, D, B, chosen);
         out->n_rounds = (int32_t)rounds.size();
         out->duration = (double*)malloc(sizeof(double) * std::max<size_t>(1, rounds.size()));
         out->dst = (int32_t*)malloc(sizeof(int32_t) * std::max<size_t>(1, rounds.size() * n));
         out->dest_order = (int32_t*)malloc(sizeof(int32_t) * (size_t)n * n);
+        out->alg1_order = (int32_t*)malloc(sizeof(int32_t) * (size_t)n * n);
         out->start = (double*)malloc(sizeof(double) * (size_t)n * n);
-        if (!out->duration || !out->dst || !out->dest_order || !out->start) {
+        if (!out->duration || !out->dst || !out->dest_order || !out->alg1_order || !out->start) {
             aurora_schedule_free(out);
             return moe_set_error(MOE_ENOMEM, "aurora_order: host allocation failed");
         }
@@ -329,7 +495,8 @@ extern "C" int aurora_order(int32_t n, const int64_t* D, const double* B, aurora
             memcpy(out->dst + r * n, rounds[r].dst.data(), sizeof(int32_t) * n);
         }
         out->makespan_rounds = total;
-        memcpy(out->dest_order, order.data(), sizeof(int32_t) * (size_t)n * n);
+        memcpy(out->dest_order, chosen.data(), sizeof(int32_t) * (size_t)n * n);
+        memcpy(out->alg1_order, order.data(), sizeof(int32_t) * (size_t)n * n);
         memcpy(out->start, start.data(), sizeof(double) * (size_t)n * n);
     } catch (const std::bad_alloc&) {
         aurora_schedule_free(out);
@@ -395,39 +562,7 @@ extern "C" int aurora_simulate(int32_t n, const int64_t* D, const double* B, con
         }
     }
     try {
-        std::vector<int> pos(n, 0), cur(n, -1);
-        std::vector<double> left(n, 0.0), rate(n, 0.0);
-        auto next_flow = [&](int i) {
-            cur[i] = -1;
-            while (pos[i] < n) {
-                const int j = order[i * n + pos[i]++];
-                if (j != i && D[i * n + j] > 0) { cur[i] = j; left[i] = (double)D[i * n + j]; break; }
-            }
-        };
-        for (int i = 0; i < n; ++i) next_flow(i);
-        double t = 0.0;
-        for (;;) {
-            std::vector<int> fan(n, 0);
-            bool any = false;
-            for (int i = 0; i < n; ++i)
-                if (cur[i] >= 0) { ++fan[cur[i]]; any = true; }
-            if (!any) break;
-            double dt = -1.0;
-            for (int i = 0; i < n; ++i) {
-                if (cur[i] < 0) continue;
-                const double bs = B ? B[i] : 1.0, br = B ? B[cur[i]] : 1.0;
-                rate[i] = std::min(bs, br / fan[cur[i]]);
-                const double need = left[i] / rate[i];
-                dt = (dt < 0.0) ? need : std::min(dt, need);
-            }
-            t += dt;
-            for (int i = 0; i < n; ++i) {
-                if (cur[i] < 0) continue;
-                left[i] -= rate[i] * dt;
-                if (left[i] <= 1e-9 * (double)D[i * n + cur[i]]) next_flow(i);
-            }
-        }
-        *time_out = t;
+        *time_out = simulate_order(n, D, B, order);
     } catch (const std::bad_alloc&) {
         return moe_set_error(MOE_ENOMEM, "aurora_simulate: host allocation failed");
     }

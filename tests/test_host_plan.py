@@ -49,15 +49,26 @@ def test_aurora_order_homogeneous_matches_oracle_exactly(n):
         check_rounds(plan, D, None, exact=True)
         assert plan["bmax"] == float(OS.bmax(D)) == plan["port_bound"]
         ref = OS.alg1_order(D)
-        assert plan["dest_order"].tolist() == ref["dest_order"]                 # same stated reading
+        assert plan["alg1_order"].tolist() == ref["dest_order"]                 # same stated reading
         assert plan["makespan_order"] == float(ref["makespan"])
         for i in range(n):
             for j in range(n):
                 s = ref["start"][i][j]
                 assert plan["start"][i, j] == (-1.0 if s is None else float(s))
         # the fluid simulation divides rates by fan-in, so doubles round where the oracle's rationals do not
-        assert P.aurora_simulate(D, None, plan["dest_order"]) == pytest.approx(
+        assert P.aurora_simulate(D, None, plan["alg1_order"]) == pytest.approx(
             float(OS.simulate(D, None, ref["dest_order"])), rel=1e-12)
+        # the order for the send buffer: candidates, choice and improvement as in the oracle (n = 16 costs the
+        # exact-rational oracle a minute, so its improvement step is compared up to n = 8)
+        if n <= 8:
+            so = OS.send_order(D)
+            assert plan["candidate_time"] == pytest.approx([float(v) for v in so["candidate_times"]], rel=1e-12)
+            assert plan["order_source"] == so["source"]
+            assert plan["dest_order"].tolist() == so["dest_order"]
+            assert plan["order_time"] == pytest.approx(float(so["time"]), rel=1e-12)
+        assert plan["order_time"] == pytest.approx(P.aurora_simulate(D, None, plan["dest_order"]), rel=1e-12)
+        assert plan["order_time"] <= min(plan["candidate_time"]) * (1 + 1e-12)
+        assert plan["order_time"] >= plan["bmax"] * (1 - 1e-12)
 
 
 @pytest.mark.parametrize("n", [2, 3, 4, 8, 16])
@@ -82,8 +93,15 @@ def test_aurora_order_heterogeneous(n):
                 tl.sort()
                 assert all(a1 >= b0 - 1e-9 for (_, b0), (a1, _) in zip(tl[:-1], tl[1:]))
         assert plan["makespan_order"] >= plan["bmax"] * (1 - 1e-12)
+        got = P.aurora_simulate(D, B, plan["alg1_order"])
+        assert got == pytest.approx(float(OS.simulate(D, B, plan["alg1_order"].tolist())), rel=1e-9)
+        assert got >= plan["port_bound"] * (1 - 1e-9)
+        for i in range(n):
+            assert sorted(plan["alg1_order"][i].tolist()) == list(range(n))
         got = P.aurora_simulate(D, B, plan["dest_order"])
+        assert got == pytest.approx(plan["order_time"], rel=1e-12)
         assert got == pytest.approx(float(OS.simulate(D, B, plan["dest_order"].tolist())), rel=1e-9)
+        assert got <= min(plan["candidate_time"]) * (1 + 1e-12)
         # with unequal rates a fast receiver can serve two slow senders at once, so the fluid model can
         # beat the one-sender-per-receiver bound of Appendix B; the per-port bound still holds
         assert got >= plan["port_bound"] * (1 - 1e-9)
@@ -105,6 +123,21 @@ def test_simulate_all_orders_against_oracle_n4_and_figure():
     assert P.aurora_simulate(fig, None, [[1, 2, 0], [2, 0, 1], [0, 1, 2]]) == 2.0
     plan = P.aurora_order(fig)
     assert plan["bmax"] == 2.0 and plan["makespan_rounds"] == 2.0 and plan["makespan_order"] == 2.0
+    assert plan["order_time"] == 2.0
+
+
+def test_send_order_against_the_stored_brute_force_optimum():
+    # the same stored cases as the oracle's pin (tests/golden/order_ratios.txt): the library's send order is never
+    # better than the optimum over all whole-flow orders, and equals what the oracle's send order reaches
+    from tests.test_oracle_schedule import load_order_ratios
+    at_optimum = 0
+    for D, B, bm, best, _alg1, send in load_order_ratios():
+        plan = P.aurora_order(D, None if B is None else [float(b) for b in B])
+        assert plan["bmax"] == pytest.approx(float(bm), rel=1e-12)
+        assert plan["order_time"] >= float(best) * (1 - 1e-9)
+        assert plan["order_time"] == pytest.approx(float(send), rel=1e-9)
+        at_optimum += abs(plan["order_time"] - float(best)) <= 1e-9 * float(best)
+    assert at_optimum == 20
 
 
 def test_schedules_for_the_workload_matrices():
