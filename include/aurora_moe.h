@@ -79,14 +79,21 @@ typedef struct {
  * (4 bytes per slot plus a few KB), allocated once in moe_ctx_create on the
  * current device.  A context must not be used by two streams at once.
  *
- * The context caches the slot ranks computed by moe_traffic: a following
- * moe_dispatch that is given the SAME topk_idx pointer reuses them and is a single
- * kernel.  moe_route marks the cache stale (it rewrites the indices), and
- * moe_dispatch recomputes the ranks itself whenever the cache is stale or was made
- * for another pointer.  A caller that rewrites topk_idx in place by other means
- * must call moe_ctx_invalidate (or moe_traffic) before the next moe_dispatch. */
+ * moe_traffic and moe_dispatch both need the rank of every slot inside its
+ * expert.  By default each computes it for itself, so a dispatch never depends
+ * on what an earlier call saw.  moe_ctx_set_rank_reuse(ctx, 1) lets a
+ * moe_dispatch / moe_dispatch_chunks reuse the ranks of a moe_traffic when that
+ * moe_traffic was given the SAME topk_idx pointer and no moe_route, dispatch,
+ * moe_ctx_invalidate or moe_ctx_set_rank_reuse came in between; the dispatch is
+ * then a single kernel.  The ranks are used once: the next dispatch computes its
+ * own unless another moe_traffic precedes it.  With reuse on, the caller
+ * promises that the indices at that address are not rewritten between the two
+ * calls by anything but this library (the check is on the pointer value, which
+ * an allocator may hand out again), and that the two calls are captured into a
+ * HIP graph together or not at all.  moe_ctx_invalidate drops the ranks. */
 typedef struct moe_ctx moe_ctx;
 int moe_ctx_create(moe_ctx** out, const moe_shape* shape);
+int moe_ctx_set_rank_reuse(moe_ctx* ctx, int32_t enable);
 int moe_ctx_invalidate(moe_ctx* ctx);
 int moe_ctx_destroy(moe_ctx* ctx); /* NULL is accepted */
 
@@ -150,7 +157,7 @@ int moe_chunk_plan_destroy(moe_chunk_plan* plan);
  *   piece_offset  device [nc+E+1] out, piece_expert device [nc+E] out, n_pieces device [1] out:
  *                 a piece is a maximal run of rows of one chunk and one expert, listed in
  *                 buffer order; piece_offset[n_pieces] is the row count
- * Other arguments, context caching and error behaviour as for moe_dispatch. */
+ * Other arguments, rank reuse and error behaviour as for moe_dispatch. */
 int moe_dispatch_chunks(moe_ctx* ctx, const moe_chunk_plan* plan, const void* x, const int32_t* topk_idx,
                         void* send_buf, int32_t* slot_to_row, int32_t* row_to_slot, int32_t* chunk_offset,
                         int32_t* piece_offset, int32_t* piece_expert, int32_t* n_pieces, void* stream);
@@ -207,6 +214,25 @@ int moe_expert_ffn_timed(const void* recv, int32_t R, const int32_t* seg_offset,
  *   y           device [T,H] dtype out (fp32 accumulation, rounded once) */
 int moe_combine(moe_ctx* ctx, const void* ret, const int32_t* slot_to_row, const float* topk_w,
                 const void* shared_out, void* y, void* stream);
+
+/* ------------------------------------------------------------------ diagnostics
+ * Host-side self checks used by the CPU tests; they launch nothing and are not needed to run the layer.
+ * Not thread-safe beyond what the rest of the library is: the FFN launch path keeps the number of compute
+ * units of the device it first ran on and the "LDS size raised" marks in process-wide statics, i.e. it
+ * assumes one kind of device per process. */
+
+/* Tile numbering and tail plan of the bf16 FFN GEMM for a tiles_m x tiles_n grid with nk k-tiles (nk even)
+ * on ncu compute units: checks that every tile is produced exactly once, whole or as pieces that cover its
+ * k-tiles exactly once.  Returns the number of pieces a tail tile is cut into (1 = no tail), or a negative
+ * moe_status. */
+int moe_selfcheck_tile_order(int32_t tiles_m, int32_t tiles_n, int32_t ncu, int32_t nk);
+
+/* Tile map of the FFN for a segment list (HOST seg_offset [nseg+1], seg_expert [nseg]; R rows, tiles of bm
+ * rows, n_local experts; gather = chain the segments of an expert into full tiles): runs the steps of the
+ * device kernel on the host and checks that every row of every non-empty segment of a known expert lies in
+ * exactly one tile of that expert.  Returns the number of tiles or a negative moe_status. */
+int moe_selfcheck_tile_map(const int32_t* seg_offset, const int32_t* seg_expert, int32_t nseg, int32_t R, int32_t bm,
+                           int32_t n_local, int32_t gather);
 
 /* ------------------------------------------------------------------ host planners */
 

@@ -37,6 +37,7 @@ SIGNATURES = {
     "moe_ctx_create": (C.c_int, [C.POINTER(_vp), C.POINTER(moe_shape)]),
     "moe_ctx_destroy": (C.c_int, [_vp]),
     "moe_ctx_invalidate": (C.c_int, [_vp]),
+    "moe_ctx_set_rank_reuse": (C.c_int, [_vp, _i32]),
     "moe_route": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "moe_traffic": (C.c_int, [_vp, _vp, C.POINTER(_i32), _vp, _vp, _vp, _vp]),
     "moe_dispatch": (C.c_int, [_vp, _vp, _vp, C.POINTER(_i32), C.POINTER(_i32), _vp, _vp, _vp, _vp, _vp, _vp]),
@@ -49,6 +50,8 @@ SIGNATURES = {
     "moe_expert_ffn_timed": (C.c_int, [_vp, _i32, _vp, _vp, _i32, C.POINTER(moe_expert_w), _i32, _i32, _i32, _i32, _i32,
                                        _vp, _vp, _sz, _vp, C.POINTER(C.c_float)]),
     "moe_combine": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "moe_selfcheck_tile_order": (C.c_int, [_i32, _i32, _i32, _i32]),
+    "moe_selfcheck_tile_map": (C.c_int, [_pi32, _pi32, _i32, _i32, _i32, _i32, _i32]),
     "aurora_order": (C.c_int, [_i32, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(aurora_schedule)]),
     "aurora_schedule_free": (None, [C.POINTER(aurora_schedule)]),
     "aurora_chunks": (C.c_int, [C.POINTER(aurora_schedule), C.POINTER(C.c_int64), C.POINTER(C.c_double), _i32,

@@ -59,8 +59,12 @@ class MoeCtx:
         self.handle = C.c_void_p()
         _check("moe_ctx_create", self.lib.moe_ctx_create(C.byref(self.handle), C.byref(self.shape)))
 
+    def set_rank_reuse(self, enable=True):
+        """Let a dispatch that directly follows a moe_traffic on the same index array reuse its slot ranks."""
+        _check("moe_ctx_set_rank_reuse", self.lib.moe_ctx_set_rank_reuse(self.handle, 1 if enable else 0))
+
     def invalidate(self):
-        """Forget cached slot ranks (needed only after rewriting topk_idx in place outside the library)."""
+        """Forget cached slot ranks (needed only with rank reuse on, after rewriting topk_idx in place)."""
         _check("moe_ctx_invalidate", self.lib.moe_ctx_invalidate(self.handle))
 
     def close(self):

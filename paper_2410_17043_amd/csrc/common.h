@@ -13,6 +13,7 @@
 #define MOE_SLOTS_PER_BLOCK 1024   // counting-scan granularity: 4 waves x 4 rounds x 64 lanes
 
 int moe_set_error(int status, const char* fmt, ...);
+int moe_check_shape(const moe_shape* s);   // the checks of moe_ctx_create
 
 #define MOE_HIP(call)                                                                     \
     do {                                                                                  \
@@ -35,7 +36,8 @@ struct moe_ctx {
     int32_t* block_hist;  // device [n_blocks][E]: slots per expert in each block, later its exclusive prefix
     int32_t* raw_count;   // device [E]: slots per expert before the capacity rule
     int32_t* slot_rank;   // device [n_slots]: rank of a slot among the slots of its expert (-1: index out of range)
-    const void* rank_src; // host: the topk_idx pointer slot_rank was computed from, NULL if stale
+    const void* rank_src; // host: the topk_idx pointer the LAST call on this context (a moe_traffic) ranked, else NULL
+    bool reuse_ranks;     // host: moe_ctx_set_rank_reuse; off unless the caller asks
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // 16-byte load/store unit

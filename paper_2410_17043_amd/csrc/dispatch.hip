@@ -20,6 +20,7 @@
 // rows of its kept slots (16-byte lanes, 1 KB per wave access, streaming loads/stores).
 #include "common.h"
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -223,6 +224,9 @@ __global__ __launch_bounds__(1024) void small_rank_kernel(const int32_t* __restr
         // many experts: nine ballots per round give every lane the lanes with the same expert; the wave's
         // running counts sit in its row of wave_cnt (only this wave touches it until the barrier below)
         for (int i = lane; i < E; i += 64) wave_cnt[wave][i] = 0;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
         for (int r = 0; r < kSmallRounds; ++r) {
             if (r < rounds) {
@@ -234,6 +238,10 @@ __global__ __launch_bounds__(1024) void small_rank_kernel(const int32_t* __restr
                     my_rank[r] = before + rk;
                     if (rk == 0) wave_cnt[wave][e] = before + __popcll(peers);
                 }
+                // the next round's lanes read counts that other lanes of this wave wrote in this one
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             }
         }
     }
@@ -580,26 +588,62 @@ int build_segmap(const moe_shape& s, const int32_t* expert_to_gpu, const int32_t
     return MOE_OK;
 }
 
+// Scratch of the counting sort: owned by a context, or the static array of moe_dispatch_noalloc.
+struct RankScratch {
+    int32_t* block_hist;   // [n_blocks][E]
+    int32_t* raw_count;    // [E]
+    int32_t* slot_rank;    // [n_slots]
+};
+
 // Rank pass; the three count outputs may be NULL.
-int launch_rank_pass(moe_ctx* c, const int32_t* idx, const SegMap& map, int32_t* expert_count, int32_t* dest_count,
-                     int32_t* n_dropped, hipStream_t st) {
-    const moe_shape& s = c->s;
-    if (c->n_slots <= kSmallMaxSlots) {
-        hipLaunchKernelGGL(small_rank_kernel, dim3(1), dim3(1024), 0, st, idx, c->n_slots, s.E, s.G, s.capacity, map,
-                           c->raw_count, c->slot_rank, expert_count, dest_count, n_dropped);
+int launch_rank_pass(const moe_shape& s, const RankScratch& sc, const int32_t* idx, const SegMap& map, int32_t* expert_count,
+                     int32_t* dest_count, int32_t* n_dropped, hipStream_t st) {
+    const int n_slots = s.T * s.k;
+    const int n_blocks = (n_slots + MOE_SLOTS_PER_BLOCK - 1) / MOE_SLOTS_PER_BLOCK;
+    if (n_slots <= kSmallMaxSlots) {
+        hipLaunchKernelGGL(small_rank_kernel, dim3(1), dim3(1024), 0, st, idx, n_slots, s.E, s.G, s.capacity, map,
+                           sc.raw_count, sc.slot_rank, expert_count, dest_count, n_dropped);
         MOE_LAUNCH_CHECK("small_rank_kernel");
     } else {
         const size_t lds = (size_t)kChunks * s.E * sizeof(int);
-        hipLaunchKernelGGL(count_kernel, dim3(c->n_blocks), dim3(256), lds, st, idx, c->n_slots, s.E, c->block_hist);
+        hipLaunchKernelGGL(count_kernel, dim3(n_blocks), dim3(256), lds, st, idx, n_slots, s.E, sc.block_hist);
         MOE_LAUNCH_CHECK("count_kernel");
-        hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(256), 0, st, c->block_hist, c->n_blocks, s.E, s.G, s.capacity, map,
-                           c->raw_count, expert_count, dest_count, n_dropped);
+        hipLaunchKernelGGL(scan_kernel, dim3(1), dim3(256), 0, st, sc.block_hist, n_blocks, s.E, s.G, s.capacity, map,
+                           sc.raw_count, expert_count, dest_count, n_dropped);
         MOE_LAUNCH_CHECK("scan_kernel");
-        hipLaunchKernelGGL(rank_kernel, dim3(c->n_blocks), dim3(256), lds, st, idx, c->n_slots, s.E, c->block_hist,
-                           c->slot_rank);
+        hipLaunchKernelGGL(rank_kernel, dim3(n_blocks), dim3(256), lds, st, idx, n_slots, s.E, sc.block_hist,
+                           sc.slot_rank);
         MOE_LAUNCH_CHECK("rank_kernel");
     }
-    c->rank_src = idx;
+    return MOE_OK;
+}
+
+RankScratch scratch_of(const moe_ctx* c) { return RankScratch{c->block_hist, c->raw_count, c->slot_rank}; }
+
+// Are the ranks that moe_traffic left in the context the ones this dispatch needs?  Only when the caller
+// has switched reuse on, the traffic call was the last call on the context, and it was given the same index
+// array.  The answer is consumed: a second dispatch computes its own ranks.
+bool take_cached_ranks(moe_ctx* c, const int32_t* idx) {
+    const bool ok = c->reuse_ranks && c->rank_src != nullptr && c->rank_src == idx;
+    c->rank_src = nullptr;
+    return ok;
+}
+
+int launch_scatter(const moe_shape& s, const RankScratch& sc, const SegMap& map, const void* x, const int32_t* topk_idx,
+                   void* send_buf, int32_t* slot_to_row, int32_t* row_to_slot, int32_t* seg_offset, int32_t* seg_expert,
+                   hipStream_t st) {
+    const int row16 = (int)((int64_t)s.H * elem_size(s.dtype) / 16);
+    const dim3 grid((s.T + 3) / 4);
+    const u32x4* xs = reinterpret_cast<const u32x4*>(x);
+    u32x4* sb = reinterpret_cast<u32x4*>(send_buf);
+#define MOE_SCATTER(KK)                                                                                          \
+    hipLaunchKernelGGL(scatter_kernel<KK>, grid, dim3(256), 0, st, xs, topk_idx, sc.slot_rank, sc.raw_count, s.T, \
+                       s.k, s.E, s.capacity, map, row16, sb, slot_to_row, row_to_slot, seg_offset, seg_expert)
+    if (s.k == 1) MOE_SCATTER(1);
+    else if (s.k == 2) MOE_SCATTER(2);
+    else MOE_SCATTER(0);
+#undef MOE_SCATTER
+    MOE_LAUNCH_CHECK("scatter_kernel");
     return MOE_OK;
 }
 
@@ -609,10 +653,14 @@ extern "C" int moe_traffic(moe_ctx* ctx, const int32_t* topk_idx, const int32_t*
                            int32_t* dest_count, int32_t* n_dropped, void* stream) {
     if (!ctx || !topk_idx || !expert_to_gpu || !expert_count || !dest_count || !n_dropped)
         return moe_set_error(MOE_EINVAL, "moe_traffic: NULL argument");
+    ctx->rank_src = nullptr;
     SegMap map;
     int rc = build_segmap(ctx->s, expert_to_gpu, nullptr, &map);
     if (rc != MOE_OK) return rc;
-    return launch_rank_pass(ctx, topk_idx, map, expert_count, dest_count, n_dropped, reinterpret_cast<hipStream_t>(stream));
+    rc = launch_rank_pass(ctx->s, scratch_of(ctx), topk_idx, map, expert_count, dest_count, n_dropped,
+                          reinterpret_cast<hipStream_t>(stream));
+    if (rc == MOE_OK) ctx->rank_src = topk_idx;
+    return rc;
 }
 
 extern "C" int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* topk_idx, const int32_t* expert_to_gpu,
@@ -621,29 +669,18 @@ extern "C" int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* topk_idx
     if (!ctx || !x || !topk_idx || !expert_to_gpu || !dest_order || !send_buf || !slot_to_row || !row_to_slot ||
         !seg_offset || !seg_expert)
         return moe_set_error(MOE_EINVAL, "moe_dispatch: NULL argument");
+    const bool cached = take_cached_ranks(ctx, topk_idx);
     if (!aligned16(x) || !aligned16(send_buf)) return moe_set_error(MOE_EALIGN, "moe_dispatch: x and send_buf must be 16-byte aligned");
     const moe_shape& s = ctx->s;
     SegMap map;
     int rc = build_segmap(s, expert_to_gpu, dest_order, &map);
     if (rc != MOE_OK) return rc;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    if (ctx->rank_src != topk_idx) {                     // no fresh ranks for these indices: compute them now
-        rc = launch_rank_pass(ctx, topk_idx, map, nullptr, nullptr, nullptr, st);
+    if (!cached) {
+        rc = launch_rank_pass(s, scratch_of(ctx), topk_idx, map, nullptr, nullptr, nullptr, st);
         if (rc != MOE_OK) return rc;
     }
-    const int row16 = (int)((int64_t)s.H * elem_size(s.dtype) / 16);
-    const dim3 grid((s.T + 3) / 4);
-    const u32x4* xs = reinterpret_cast<const u32x4*>(x);
-    u32x4* sb = reinterpret_cast<u32x4*>(send_buf);
-#define MOE_SCATTER(KK)                                                                                          \
-    hipLaunchKernelGGL(scatter_kernel<KK>, grid, dim3(256), 0, st, xs, topk_idx, ctx->slot_rank, ctx->raw_count, s.T, \
-                       s.k, s.E, s.capacity, map, row16, sb, slot_to_row, row_to_slot, seg_offset, seg_expert)
-    if (s.k == 1) MOE_SCATTER(1);
-    else if (s.k == 2) MOE_SCATTER(2);
-    else MOE_SCATTER(0);
-#undef MOE_SCATTER
-    MOE_LAUNCH_CHECK("scatter_kernel");
-    return MOE_OK;
+    return launch_scatter(s, scratch_of(ctx), map, x, topk_idx, send_buf, slot_to_row, row_to_slot, seg_offset, seg_expert, st);
 }
 
 struct moe_chunk_plan {
@@ -731,13 +768,14 @@ extern "C" int moe_dispatch_chunks(moe_ctx* ctx, const moe_chunk_plan* plan, con
     if (!ctx || !plan || !x || !topk_idx || !send_buf || !slot_to_row || !row_to_slot || !chunk_offset || !piece_offset ||
         !piece_expert || !n_pieces)
         return moe_set_error(MOE_EINVAL, "moe_dispatch_chunks: NULL argument");
+    const bool cached = take_cached_ranks(ctx, topk_idx);
     if (!aligned16(x) || !aligned16(send_buf))
         return moe_set_error(MOE_EALIGN, "moe_dispatch_chunks: x and send_buf must be 16-byte aligned");
     const moe_shape& s = ctx->s;
     if (plan->E != s.E || plan->G != s.G) return moe_set_error(MOE_ESHAPE, "moe_dispatch_chunks: plan made for another shape");
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    if (ctx->rank_src != topk_idx) {                     // no fresh ranks for these indices: compute them now
-        int rc = launch_rank_pass(ctx, topk_idx, plan->map, nullptr, nullptr, nullptr, st);
+    if (!cached) {
+        int rc = launch_rank_pass(s, scratch_of(ctx), topk_idx, plan->map, nullptr, nullptr, nullptr, st);
         if (rc != MOE_OK) return rc;
     }
     hipLaunchKernelGGL(chunk_layout_kernel, dim3(1), dim3(kLayoutThreads), 0, st, plan->tb, ctx->raw_count, s.E, s.G,

@@ -27,7 +27,7 @@ extern "C" const char* moe_status_str(int status) {
     }
 }
 
-static int check_shape(const moe_shape* s) {
+int moe_check_shape(const moe_shape* s) {
     if (!s) return moe_set_error(MOE_EINVAL, "shape is NULL");
     if (s->T <= 0 || s->H <= 0 || s->E <= 0 || s->k <= 0 || s->G <= 0)
         return moe_set_error(MOE_EINVAL, "T, H, E, k, G must be positive");
@@ -43,7 +43,7 @@ static int check_shape(const moe_shape* s) {
 extern "C" int moe_ctx_create(moe_ctx** out, const moe_shape* shape) {
     if (!out) return moe_set_error(MOE_EINVAL, "out is NULL");
     *out = nullptr;
-    int rc = check_shape(shape);
+    int rc = moe_check_shape(shape);
     if (rc != MOE_OK) return rc;
     moe_ctx* c = new (std::nothrow) moe_ctx();
     if (!c) return moe_set_error(MOE_ENOMEM, "host allocation failed");
@@ -52,6 +52,7 @@ extern "C" int moe_ctx_create(moe_ctx** out, const moe_shape* shape) {
     c->n_blocks = (c->n_slots + MOE_SLOTS_PER_BLOCK - 1) / MOE_SLOTS_PER_BLOCK;
     c->block_hist = nullptr;
     c->rank_src = nullptr;
+    c->reuse_ranks = false;
     size_t bytes = ((size_t)c->n_blocks * shape->E + shape->E + (size_t)c->n_slots) * sizeof(int32_t);
     hipError_t e = hipMalloc((void**)&c->block_hist, bytes);
     if (e != hipSuccess) {
@@ -66,6 +67,13 @@ extern "C" int moe_ctx_create(moe_ctx** out, const moe_shape* shape) {
 
 extern "C" int moe_ctx_invalidate(moe_ctx* ctx) {
     if (!ctx) return moe_set_error(MOE_EINVAL, "moe_ctx_invalidate: ctx is NULL");
+    ctx->rank_src = nullptr;
+    return MOE_OK;
+}
+
+extern "C" int moe_ctx_set_rank_reuse(moe_ctx* ctx, int32_t enable) {
+    if (!ctx) return moe_set_error(MOE_EINVAL, "moe_ctx_set_rank_reuse: ctx is NULL");
+    ctx->reuse_ranks = enable != 0;
     ctx->rank_src = nullptr;
     return MOE_OK;
 }

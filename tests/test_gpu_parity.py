@@ -174,7 +174,8 @@ def test_traffic_and_dispatch(H, cfg, cap):
 @pytest.mark.parametrize("cfg", [small("c2_mixtral", T=700, H=264), small("c5_finegrained", T=3000, H=64)],
                          ids=lambda c: c.name)
 def test_dispatch_alone_and_after_in_place_index_rewrite(H, cfg):
-    """moe_dispatch without a preceding moe_traffic, and the stale-cache rules of the context."""
+    """moe_dispatch never depends on an earlier call unless rank reuse was switched on; with reuse on, the
+    ranks of a moe_traffic serve exactly one directly following dispatch on the same index array."""
     inp = W.make_layer_inputs(cfg)
     e2g = inp["expert_to_gpu"]
     order = list(np.random.default_rng(3).permutation(cfg.G))
@@ -193,15 +194,38 @@ def test_dispatch_alone_and_after_in_place_index_rewrite(H, cfg):
     sh.idx.copy_(torch.from_numpy(idx_a))
     sh.dispatch(x, e2g, order)                                     # fresh context: ranks computed inside
     check(idx_a)
-    sh.traffic(e2g)                                                # caches ranks for idx_a
-    sh.idx.copy_(torch.from_numpy(idx_b))                          # rewritten in place behind the library's back
+    # default (no reuse): indices rewritten in place behind the library's back, no invalidate: still right
+    sh.traffic(e2g)
+    sh.idx.copy_(torch.from_numpy(idx_b))
+    sh.dispatch(x, e2g, order)
+    check(idx_b)
+    # reuse on: traffic then dispatch (one kernel) is right ...
+    sh.ctx.set_rank_reuse(True)
+    sh.traffic(e2g)
+    sh.dispatch(x, e2g, order)
+    check(idx_b)
+    # ... the ranks are used once: a rewrite after that dispatch cannot reach a stale rank
+    sh.idx.copy_(torch.from_numpy(idx_a))
+    sh.dispatch(x, e2g, order)
+    check(idx_a)
+    # ... a rewrite between traffic and dispatch is the caller's to announce
+    sh.traffic(e2g)
+    sh.idx.copy_(torch.from_numpy(idx_b))
     sh.ctx.invalidate()
     sh.dispatch(x, e2g, order)
     check(idx_b)
-    other = sh.idx.clone()                                         # same contents, another pointer: never served from cache
+    # ... and ranks made for another pointer are never used
+    sh.traffic(e2g)
+    other = sh.idx.clone()
     other.copy_(torch.from_numpy(idx_a))
     H.P.moe_dispatch(sh.ctx, x, other, e2g, order, sh.send_buf, sh.slot_to_row, sh.row_to_slot, sh.seg_offset,
                      sh.seg_expert)
+    check(idx_a)
+    # ... nor after a moe_route on the context (it rewrites the indices)
+    sh.idx.copy_(torch.from_numpy(idx_b))
+    sh.traffic(e2g)
+    sh.route(x, H.dev(inp["w_gate"], cfg.dtype), None if inp["gate_bias"] is None else torch.from_numpy(inp["gate_bias"]).float().to(H.DEV))
+    sh.dispatch(x, e2g, order)
     check(idx_a)
 
 
