@@ -135,6 +135,26 @@ int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* topk_idx, const int
                  const int32_t* dest_order, void* send_buf, int32_t* slot_to_row,
                  int32_t* row_to_slot, int32_t* seg_offset, int32_t* seg_expert, void* stream);
 
+/* moe_dispatch for callers that cannot allocate device memory: code that runs
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * It needs no context: the scratch of the counting sort (block histograms,
+ * per-expert totals, 4 bytes per slot) lives in a static device array of
+ * 5 MiB + 1 KiB that every GPU the library runs on holds until the process ends.
+ * The call allocates and frees nothing, on the device or through any library.
+ *   shape        HOST, the checks of moe_ctx_create apply; additionally
+ *                T*k <= 1048576 slots, else MOE_ESHAPE (use moe_dispatch)
+ *   other arguments, layouts and results exactly as moe_dispatch
+ * The ranks are always computed by the call itself (nothing is reused from
+ * moe_traffic).  All calls on one GPU share that GPU's array: two calls that
+ * overlap in time on one GPU (two streams, two threads) race; calls on one stream
+ * are ordered by the stream.  Nothing in the array needs clearing between calls:
+ * each call writes every word it later reads.  The array's device address is
+ * looked up on the first call on each device (current device = the stream's). */
+int moe_dispatch_noalloc(const moe_shape* shape, const void* x, const int32_t* topk_idx,
+                         const int32_t* expert_to_gpu, const int32_t* dest_order, void* send_buf,
+                         int32_t* slot_to_row, int32_t* row_to_slot, int32_t* seg_offset, int32_t* seg_expert,
+                         void* stream);
+
 /* A preemptive send plan (Appendix A; see aurora_chunks): chunk c carries the
  * next chunk_rows[c] slots of destination chunk_dest[c].  The slots of a
  * destination form one sequence - expert by expert (ascending id), inside an

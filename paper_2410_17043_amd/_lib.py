@@ -41,6 +41,8 @@ SIGNATURES = {
     "moe_route": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "moe_traffic": (C.c_int, [_vp, _vp, C.POINTER(_i32), _vp, _vp, _vp, _vp]),
     "moe_dispatch": (C.c_int, [_vp, _vp, _vp, C.POINTER(_i32), C.POINTER(_i32), _vp, _vp, _vp, _vp, _vp, _vp]),
+    "moe_dispatch_noalloc": (C.c_int, [C.POINTER(moe_shape), _vp, _vp, C.POINTER(_i32), C.POINTER(_i32), _vp, _vp, _vp, _vp,
+                                       _vp, _vp]),
     "moe_chunk_plan_create": (C.c_int, [_vp, C.POINTER(_i32), _i32, C.POINTER(_i32), C.POINTER(_i32), C.POINTER(_vp)]),
     "moe_chunk_plan_destroy": (C.c_int, [_vp]),
     "moe_dispatch_chunks": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),

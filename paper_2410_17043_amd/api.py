@@ -155,6 +155,18 @@ def moe_dispatch(ctx, x, topk_idx, expert_to_gpu, dest_order, send_buf, slot_to_
                                                 _ptr(seg_expert), _stream()))
 
 
+def moe_dispatch_noalloc(shape, x, topk_idx, expert_to_gpu, dest_order, send_buf, slot_to_row, row_to_slot, seg_offset,
+                         seg_expert):
+    """moe_dispatch without a context: `shape` is (T, H, E, k, G, dtype, renorm, capacity)."""
+    T, H, E, k, G, dtype, renorm, capacity = shape
+    sh = moe_shape(T, H, E, k, G, _DT[dtype], renorm, capacity)
+    _a, e2g = _i32_array(expert_to_gpu)
+    _b, order = _i32_array(dest_order)
+    _check("moe_dispatch_noalloc", _lib.load().moe_dispatch_noalloc(
+        C.byref(sh), _ptr(x), _ptr(topk_idx), e2g, order, _ptr(send_buf), _ptr(slot_to_row), _ptr(row_to_slot),
+        _ptr(seg_offset), _ptr(seg_expert), _stream()))
+
+
 class MoeChunkPlan:
     """Owner of a moe_chunk_plan: a preemptive send plan [(dest, rows), ...] for one GPU."""
 

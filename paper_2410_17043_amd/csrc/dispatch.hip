@@ -683,6 +683,73 @@ extern "C" int moe_dispatch(moe_ctx* ctx, const void* x, const int32_t* topk_idx
     return launch_scatter(s, scratch_of(ctx), map, x, topk_idx, send_buf, slot_to_row, row_to_slot, seg_offset, seg_expert, st);
 }
 
+// ---------------------------------------------------------------------------- no allocation
+// moe_dispatch for callers that cannot allocate: the counting-sort scratch that a context would own
+// lives in a static device array.  Every GPU holds its own copy at its own address; the host looks the
+// address up once per device and passes that pointer to the kernels (the array's name means nothing
+// on the host side).
+constexpr int kNoAllocMaxSlots = 1 << 20;
+constexpr int kNoAllocMaxBlocks = kNoAllocMaxSlots / MOE_SLOTS_PER_BLOCK;
+constexpr size_t kNoAllocWords = (size_t)kNoAllocMaxBlocks * MOE_MAX_E + MOE_MAX_E + kNoAllocMaxSlots;   // 5 MiB + 1 KiB
+static __device__ __align__(256) int32_t scratch[kNoAllocWords];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+int32_t* g_scratch_ptr[kMaxDevices];        // per device: address of `scratch` there, nullptr until looked up
+
+int scratch_for_current_device(int32_t** out) {
+    int dev = -1;
+    MOE_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return moe_set_error(MOE_ESHAPE, "moe_dispatch_noalloc: device %d outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        MOE_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return moe_set_error(MOE_EHIP, "moe_dispatch_noalloc: hipGetSymbolAddress returned no address");
+        g_scratch_ptr[dev] = reinterpret_cast<int32_t*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return MOE_OK;
+}
+}  // namespace
+
+extern "C" int moe_dispatch_noalloc(const moe_shape* shape, const void* x, const int32_t* topk_idx,
+                                    const int32_t* expert_to_gpu, const int32_t* dest_order, void* send_buf,
+                                    int32_t* slot_to_row, int32_t* row_to_slot, int32_t* seg_offset, int32_t* seg_expert,
+                                    void* stream) {
+    if (!shape || !x || !topk_idx || !expert_to_gpu || !dest_order || !send_buf || !slot_to_row || !row_to_slot ||
+        !seg_offset || !seg_expert)
+        return moe_set_error(MOE_EINVAL, "moe_dispatch_noalloc: NULL argument");
+    int rc = moe_check_shape(shape);
+    if (rc != MOE_OK) return rc;
+    const moe_shape& s = *shape;
+    if ((int64_t)s.T * s.k > kNoAllocMaxSlots)
+        return moe_set_error(MOE_ESHAPE, "moe_dispatch_noalloc: T*k = %lld exceeds the static scratch (%d slots); use moe_dispatch",
+                             (long long)s.T * s.k, kNoAllocMaxSlots);
+    if (!aligned16(x) || !aligned16(send_buf))
+        return moe_set_error(MOE_EALIGN, "moe_dispatch_noalloc: x and send_buf must be 16-byte aligned");
+    SegMap map;
+    rc = build_segmap(s, expert_to_gpu, dest_order, &map);
+    if (rc != MOE_OK) return rc;
+    int32_t* base = nullptr;
+    rc = scratch_for_current_device(&base);
+    if (rc != MOE_OK) return rc;
+    // same layout as a context's scratch; every word a kernel reads is written earlier in the same call
+    // (block histograms for every block, totals for every expert, a rank for every slot), so nothing has
+    // to be cleared and what an earlier call left behind is never seen
+    const int n_slots = s.T * s.k;
+    const int n_blocks = (n_slots + MOE_SLOTS_PER_BLOCK - 1) / MOE_SLOTS_PER_BLOCK;
+    RankScratch sc;
+    sc.block_hist = base;
+    sc.raw_count = base + (size_t)n_blocks * s.E;
+    sc.slot_rank = sc.raw_count + s.E;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    rc = launch_rank_pass(s, sc, topk_idx, map, nullptr, nullptr, nullptr, st);
+    if (rc != MOE_OK) return rc;
+    return launch_scatter(s, sc, map, x, topk_idx, send_buf, slot_to_row, row_to_slot, seg_offset, seg_expert, st);
+}
+
 struct moe_chunk_plan {
     SegMap map;
     ChunkTables tb;
