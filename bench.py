@@ -24,12 +24,27 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM-side bytes per launch of the first FFN GEMM at c2_mixtral from rocprofv3 counters (FETCH_SIZE x 2.0 +
-# WRITE_SIZE x 1.0, see profiles/bench_c2_mixtral_layer_share.md); None once the kernel has changed since.
-GEMM1_TRAFFIC_BYTES = {"c2_mixtral": 3.9033e6 * 1024 * 2.0 + 6.6752e5 * 1024}
+# WRITE_SIZE x 1.0, see profiles/bench_c2_mixtral_layer_share.md), valid for the kernel source whose SHA-256
+# starts with the digest below; reported as null as soon as ffn.hip differs from what the counters saw.
+GEMM1_TRAFFIC = {"c2_mixtral": {"bytes": 3.9033e6 * 1024 * 2.0 + 6.6752e5 * 1024, "ffn_hip_sha256": "99a3b877377d1149"}}
 
 
-def build_workload(cfg, torch, P, W, share="bottleneck"):
-    """Everything a step needs, resident on the GPU.  Returns a dict of tensors and the step closure."""
+def gemm1_traffic_bytes(name):
+    rec = GEMM1_TRAFFIC.get(name)
+    if rec is None:
+        return None
+    import hashlib
+    with open(os.path.join(ROOT, "paper_2410_17043_amd", "csrc", "ffn.hip"), "rb") as f:
+        digest = hashlib.sha256(f.read()).hexdigest()
+    return rec["bytes"] if digest.startswith(rec["ffn_hip_sha256"]) else None
+
+
+def build_workload(cfg, torch, P, W, share="bottleneck", placement=None):
+    """Everything a step needs, resident on the GPU.  Returns a dict of tensors and the step closure.
+
+    placement = None: experts in contiguous blocks (expert e on GPU e // E_loc), the GPU under test chosen by
+    `share`.  placement = (g, unit_of_gpu): GPU p of the cluster holds the tokens and the expert block that
+    the workload generator calls GPU unit_of_gpu[p] (the result of a colocation), and GPU g is under test."""
     dev = "cuda:0"
     tdt = P.TORCH_DTYPE[cfg.dtype]
 
@@ -37,13 +52,23 @@ def build_workload(cfg, torch, P, W, share="bottleneck"):
         return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev).to(tdt).contiguous()
 
     traffic = W.make_traffic_matrix(cfg)
+    if placement is not None:
+        g, unit_of_gpu = int(placement[0]), [int(u) for u in placement[1]]
+        assert sorted(unit_of_gpu) == list(range(cfg.G))
+        traffic = {"D": traffic["D"][np.ix_(unit_of_gpu, unit_of_gpu)], "per_expert": traffic["per_expert"][unit_of_gpu]}
+    else:
+        unit_of_gpu = list(range(cfg.G))
     D = traffic["D"].copy()
     received = D.sum(axis=0)
-    if share == "median":
+    if placement is not None:
+        pass
+    elif share == "median":
         g = int(np.argsort(received, kind="stable")[len(received) // 2])
     else:
         g = int(np.argmax(received))                        # the GPU that receives most sets the layer time
-    inp = W.make_layer_inputs(cfg, g)
+    inp = W.make_layer_inputs(cfg, unit_of_gpu[g])
+    gpu_of_unit = np.argsort(np.asarray(unit_of_gpu))
+    inp["expert_to_gpu"] = gpu_of_unit[inp["expert_to_gpu"]].astype(np.int32)
     e2g = inp["expert_to_gpu"]
     local = [e for e in range(cfg.E) if e2g[e] == g]
     x, wg = to_dev(inp["x"]), to_dev(inp["w_gate"])
@@ -122,7 +147,23 @@ def build_workload(cfg, torch, P, W, share="bottleneck"):
     b_traffic = P.bind_traffic(ctx, idx, e2g, expert_count, dest_count, n_dropped)
     b_dispatch = P.bind_dispatch(ctx, x, idx, e2g, dest_order, send_buf, s2r, r2s, seg_offset, seg_expert)
     b_ffn = P.bind_expert_ffn(recv, R, ffn_off, ffn_exp, len(exp), table, H, F, cfg.act, cfg.dtype, ffn_out, ws)
-    b_combine = P.bind_combine(ctx, ret, s2r, w, None, y)
+    # shared experts (applied to every local token, weight 1): their outputs add up, which equals ONE expert
+    # whose inner dimension is the concatenation of theirs, so the weights are stacked once here and one
+    # grouped-FFN call over the local tokens feeds moe_combine's shared_out
+    shared_out, b_shared, shared_keep = None, None, None
+    if cfg.n_shared:
+        sw = [W.make_expert_weights(cfg, s_, shared=True) for s_ in range(cfg.n_shared)]
+        cat = {"w1": to_dev(np.concatenate([v["w1"] for v in sw])),
+               "w_up": to_dev(np.concatenate([v["w_up"] for v in sw])) if sw[0]["w_up"] is not None else None,
+               "w_down": to_dev(np.concatenate([v["w_down"] for v in sw], axis=1))}
+        Fs = F * cfg.n_shared
+        sh_table = P.expert_table([cat])
+        sh_off, sh_exp = torch.tensor([0, T], **i32), torch.tensor([0], **i32)
+        sh_ws = torch.empty(P.moe_ffn_workspace_bytes(T, H, Fs, cfg.act, cfg.dtype), dtype=torch.uint8, device=dev)
+        shared_out = torch.empty((T, H), dtype=tdt, device=dev)
+        b_shared = P.bind_expert_ffn(x, T, sh_off, sh_exp, 1, sh_table, H, Fs, cfg.act, cfg.dtype, shared_out, sh_ws)
+        shared_keep = (cat, sh_table, sh_off, sh_exp, sh_ws)
+    b_combine = P.bind_combine(ctx, ret, s2r, w, shared_out, y)
 
     # the same send buffer laid out for the preemptive plan of the schedule's rounds: timed beside the
     # stages for information, not part of the step (it writes buffers of its own)
@@ -137,17 +178,29 @@ def build_workload(cfg, torch, P, W, share="bottleneck"):
     def cur():
         return torch.cuda.current_stream().cuda_stream
 
-    def step():
+    def front():                                             # Gate, traffic row, send buffer, loop-back of the first all-to-all
         st = cur()
         b_route(st)
         b_traffic(st)
         b_dispatch(st)
-        for (r0, lo, hi) in self_spans:                      # loop-back part of the first all-to-all
+        for (r0, lo, hi) in self_spans:
             recv[r0:r0 + hi - lo].copy_(send_buf[lo:hi], non_blocking=True)
+
+    def ffn():                                               # routed experts over the received rows, shared experts over the local tokens
+        st = cur()
         b_ffn(st)
-        for (r0, lo, hi) in self_spans:                      # loop-back part of the second all-to-all
+        if b_shared is not None:
+            b_shared(st)
+
+    def back():                                              # loop-back of the second all-to-all, Aggregation
+        for (r0, lo, hi) in self_spans:
             ret[lo:hi].copy_(ffn_out[r0:r0 + hi - lo], non_blocking=True)
-        b_combine(st)
+        b_combine(cur())
+
+    def step():
+        front()
+        ffn()
+        back()
 
     def traffic_then(b):
         def fn():
@@ -161,20 +214,27 @@ def build_workload(cfg, torch, P, W, share="bottleneck"):
               "traffic+dispatch": traffic_then(b_dispatch),
               "expert_ffn": lambda: b_ffn(cur()), "combine": lambda: b_combine(cur()),
               "traffic+dispatch_chunks": traffic_then(b_dispatch_chunks)}
+    if b_shared is not None:
+        stages["shared_ffn"] = lambda: b_shared(cur())
     ffn_timed = lambda: P.moe_expert_ffn_timed(recv, R, ffn_off, ffn_exp, len(exp), table, H, F, cfg.act, cfg.dtype,
                                                ffn_out, ws)
     n_kept = int(so[-1])
-    return dict(step=step, stages=stages, ffn_timed=ffn_timed, R=R, g=g, n_kept=n_kept, inp=inp, y=y,
+    return dict(step=step, front=front, ffn=ffn, back=back, stages=stages, ffn_timed=ffn_timed, R=R, g=g, n_kept=n_kept, inp=inp, y=y,
+                shared_out=shared_out, x=x, unit_of_gpu=unit_of_gpu, shared_keep=shared_keep,
                 idx=idx, w=w, expert_count=expert_count, dest_count=dest_count, n_dropped=n_dropped,
                 send_buf=send_buf, slot_to_row=s2r, row_to_slot=r2s, seg_offset=seg_offset, seg_expert=seg_expert,
                 recv=recv, ffn_out=ffn_out, ret=ret, ffn_off=off, ffn_exp=exp, local=local, dest_order=dest_order,
                 self_spans=self_spans, n_chunks=len(chunks), D=D, rates=rates, plan=plan, keep=(ctx, x, wg, bias, experts, table, ws, chunk_plan))
 
 
-def box_reference(torch, wl, cfg):
-    """What this very box sustains, for orientation beside the published peaks: a plain device copy
-    (256 MiB read + 256 MiB written) and, for bf16 workloads, the vendor library's GEMM of the first FFN
-    GEMM's shape (one projection, no activation; torch.matmul -> hipBLASLt).  Neither is on the product path."""
+def box_reference(torch, wl, cfg, P):
+    """What this very box sustains, for orientation beside the published peaks.  None of it is on the product
+    path.  copy_GBps: a plain device copy (256 MiB read + 256 MiB written, torch).  copy_1r2w_GBps: the
+    library's reference kernel that reads the token block of this workload once and writes it twice with
+    streaming 16-byte accesses (the send buffer's traffic without indexing).  mfma_only_TFLOPs: the
+    library's register-only loop of independent v_mfma_f32_32x32x16_bf16 on one wave per SIMD of every compute
+    unit, about 5 ms long (no LDS, no memory traffic: the ceiling of the matrix cores at the clock this box
+    grants them).  vendor_gemm_bf16_TFLOPs: hipBLASLt's GEMM of one projection of the first FFN GEMM."""
     dev = wl["recv"].device
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
@@ -187,6 +247,21 @@ def box_reference(torch, wl, cfg):
     ev[1].synchronize()
     out = {"copy_GBps": round(5 * 2 * (256 << 20) / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9, 1)}
     del src, dst
+    x = wl["x"]
+    d0, d1 = torch.empty_like(x), torch.empty_like(x)
+    P.moe_diag_copy_1r2w(x, d0, d1)
+    ms = [P.moe_diag_copy_1r2w(x, d0, d1) for _ in range(10)]
+    nbytes = 3 * x.numel() * x.element_size()
+    out["copy_1r2w_GBps"] = round(nbytes / (float(np.mean(ms)) * 1e-3) / 1e9, 1)
+    out["copy_1r2w_us"] = round(float(np.mean(ms)) * 1e3, 2)
+    out["copy_1r2w_bytes"] = nbytes
+    del d0, d1
+    n_cu = torch.cuda.get_device_properties(dev).multi_processor_count
+    sink = torch.empty(n_cu * 256, dtype=torch.float32, device=dev)
+    P.moe_diag_mfma_only(n_cu, 1024, sink)
+    runs = [P.moe_diag_mfma_only(n_cu, 16384, sink) for _ in range(5)]
+    out["mfma_only_TFLOPs"] = round(float(np.mean([f / (m * 1e-3) / 1e12 for m, f in runs])), 1)
+    out["mfma_only_ms"] = round(float(np.mean([m for m, _ in runs])), 3)
     if cfg.dtype == "bf16":
         w1 = wl["keep"][4][0]["w1"]                              # [F, H] of the first local expert
         recv = wl["recv"]
@@ -265,33 +340,244 @@ def time_graph(torch, g, launches, per_launch):
     return a.elapsed_time(b) / (launches * per_launch)
 
 
+def blas_threads():
+    """Threads the host BLAS behind numpy uses (the oracle's matmuls run there)."""
+    try:
+        from threadpoolctl import threadpool_info
+        n = [p_.get("num_threads", 1) for p_ in threadpool_info()]
+        if n:
+            return int(max(n))
+    except Exception:
+        pass
+    return int(os.cpu_count() or 1)
+
+
+CPU_MAX_ROWS = 65536          # the oracle's FFN leg is bounded to this many received rows (10-30 s of host work)
+
+
 def cpu_baseline(cfg, wl, W):
-    """The oracle, as it stands, on the whole share (about 15 s of fp64 numpy), on this machine's host cores."""
+    """The oracle, as it stands, on the share (about 15 s of fp64 numpy at the Mixtral shape), on this machine's
+    host cores: the whole share when it has at most CPU_MAX_ROWS received rows, else the first 1/frac of its
+    local tokens and of its received rows.  Returns (seconds, tokens, rows, frac)."""
     from oracle import moe_layer as O
-    frac = 1
-    Ts = max(1, cfg.T // frac)
-    Rs = max(1, wl["R"] // frac)
+    frac = max(1, -(-wl["R"] // CPU_MAX_ROWS))
+    Ts, Rs = max(1, cfg.T // frac), max(1, wl["R"] // frac)
     inp = wl["inp"]
     x = inp["x"][:Ts]
-    experts = [W.make_expert_weights(cfg, e) for e in range(cfg.E) if inp["expert_to_gpu"][e] == wl["g"]][:1]
+    experts = [W.make_expert_weights(cfg, e) for e in wl["local"]]
+    shared = [W.make_expert_weights(cfg, s_, shared=True) for s_ in range(cfg.n_shared)]
     rows = W.generate.make_rows(cfg, W.generate.S_RECV, Rs)
+    off = [min(o, Rs) for o in wl["ffn_off"]]
+    exp = wl["ffn_exp"]
     t0 = time.perf_counter()
     idx, w, _ = O.route(x, inp["w_gate"], inp["gate_bias"], cfg.k, cfg.renorm)
     O.traffic(idx, inp["expert_to_gpu"], cfg.G, cfg.capacity)
-    d = O.dispatch(x, idx, inp["expert_to_gpu"], list(range(cfg.G)), cfg.capacity)
-    out = O.expert_ffn(rows, [0, Rs], [0], experts, cfg.act)
+    d = O.dispatch(x, idx, inp["expert_to_gpu"], list(wl["dest_order"]), cfg.capacity)
+    out = O.expert_ffn(rows, off, exp, experts, cfg.act)
+    sh = None
+    for sw in shared:
+        o = O.ffn(x, sw["w1"], sw["w_up"], sw["w_down"], cfg.act)
+        sh = o if sh is None else sh + o
     ret = np.resize(out, (d["n_rows"], cfg.H))
-    O.combine(ret, d["slot_to_row"], w)
-    dt = time.perf_counter() - t0
+    O.combine(ret, d["slot_to_row"], w, sh)
+    return time.perf_counter() - t0, Ts, Rs, frac
+
+
+def cpu_baseline_line(cfgs_wls, W):
+    parts = [cpu_baseline(cfg, wl, W) for cfg, wl in cfgs_wls]
+    dt, toks = sum(p_[0] for p_ in parts), sum(p_[1] for p_ in parts)
+    out = {"value": toks / dt, "unit": "tokens/s", "cores": blas_threads(), "kind": "oracle",
+           "sample": "1/%d of the share, one run of %.1f s: %s; fp64 numpy (matmuls in the host BLAS on `cores` threads, "
+                     "the per-token loops of route/dispatch/combine on one); the received rows are regenerated from "
+                     "the same seeds outside the timed region instead of being read back from the GPU, and the "
+                     "returned rows are the FFN output recycled to the send-buffer row count"
+                     % (parts[0][3], dt, " + ".join("%d local tokens routed/dispatched/combined in the step's transmission order, "
+                                       "%d received rows through the expert FFN" % (p_[1], p_[2]) for p_ in parts))}
+    # the tiny fp32 configuration on one thread (whole layer over its 4 simulated GPUs, per-token definition)
     try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        cores = os.cpu_count() or 1
-    return {"value": Ts / dt, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-            "sample": "1/%d of the share: %d local tokens routed/dispatched/combined and %d received rows through "
-                      "the expert FFN (inputs generated outside the timed region), fp64 numpy, one run of %.1f s"
-                      % (frac, Ts, Rs, dt)}
+        from threadpoolctl import threadpool_limits
+        from oracle import moe_layer as O
+        c1 = W.get_config("c1_tiny_fp32")
+        inputs = [W.make_layer_inputs(c1, g_) for g_ in range(c1.G)]
+        experts = [W.make_expert_weights(c1, e) for e in range(c1.E)]
+        with threadpool_limits(limits=1):
+            t0 = time.perf_counter()
+            for g_ in range(c1.G):
+                O.layer_dense(inputs[g_]["x"], inputs[0]["w_gate"], inputs[0]["gate_bias"], c1.k, c1.renorm, experts, c1.act,
+                              c1.capacity)
+            out["c1_tiny_fp32_single_thread_tokens_per_s"] = c1.G * c1.T / (time.perf_counter() - t0)
+    except Exception as e:                                   # informative only
+        out["c1_tiny_fp32_single_thread_tokens_per_s"] = None
+        out["c1_note"] = repr(e)
+    return out
+
+
+def measure_step(torch, step, outputs, args):
+    """Times `step` (HIP-graph replay unless --no-graph; replays are first checked against the eager result on
+    `outputs`).  Returns (GPU ms per step from events, wall ms per step, launch mode)."""
+    step()
+    torch.cuda.synchronize()
+    eager = [o.clone() for o in outputs]
+    use_graph = not args.no_graph
+    if use_graph:
+        g_step = capture(torch, step)
+        for _ in range(3):                                   # no memset nodes are recorded by the library; check anyway
+            for o in outputs:
+                o.zero_()
+            g_step.replay()
+            torch.cuda.synchronize()
+            if not all(torch.equal(o, e) for o, e in zip(outputs, eager)):
+                print("graph replay differs from the eager step", file=sys.stderr)
+                sys.exit(3)
+        run_step = g_step.replay
+    else:
+        run_step = step
+    for _ in range(args.warmup):
+        run_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(args.steps):
+        run_step()
+    b.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    return a.elapsed_time(b) / args.steps, wall_ms, "hip graph replay" if use_graph else "eager"
+
+
+def measure_stages(torch, wl, cfg, reps):
+    """GPU time of every stage (10 calls per graph replay; the FFN once), the FFN's kernels by HIP events, and
+    the rates against the algorithmic work."""
+    stage_ms = {}
+    for name, fn in wl["stages"].items():
+        per = 10 if name not in ("expert_ffn", "shared_ffn") else 1
+        stage_ms[name] = time_graph(torch, capture(torch, fn, per), reps, per)
+    stage_ms["dispatch"] = stage_ms.pop("traffic+dispatch") - stage_ms["traffic"]
+    stage_ms["dispatch_chunks (not in the step)"] = stage_ms.pop("traffic+dispatch_chunks") - stage_ms["traffic"]
+    gemm_ms = np.mean([wl["ffn_timed"]() for _ in range(reps)], axis=0)   # tile map, GEMM1 (+act), GEMM2
+    R, T, k, H, F, b_el = wl["R"], cfg.T, cfg.k, cfg.H, cfg.F, (2 if cfg.dtype == "bf16" else 4)
+    n_up = 2 if cfg.act == 2 else 1
+    flops_gemm1 = 2.0 * n_up * R * H * F
+    flops_gemm2 = 2.0 * R * H * F
+    bytes_dispatch = T * H * b_el + wl["n_kept"] * H * b_el + T * k * 12
+    bytes_combine = wl["n_kept"] * H * b_el + T * H * b_el + T * k * 8 + (T * H * b_el if cfg.n_shared else 0)
+    bytes_route = T * H * b_el + cfg.E * H * b_el + T * k * 8
+    rate = {
+        "route_GBps": bytes_route / (stage_ms["route"] * 1e-3) / 1e9,
+        "dispatch_GBps": bytes_dispatch / (stage_ms["dispatch"] * 1e-3) / 1e9,
+        "combine_GBps": bytes_combine / (stage_ms["combine"] * 1e-3) / 1e9,
+        "ffn_TFLOPs": (flops_gemm1 + flops_gemm2) / (stage_ms["expert_ffn"] * 1e-3) / 1e12,
+        "ffn_mfma_util": (flops_gemm1 + flops_gemm2) / (stage_ms["expert_ffn"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "gemm2_TFLOPs": flops_gemm2 / (gemm_ms[2] * 1e-3) / 1e12,
+        "tilemap_ms": float(gemm_ms[0]),
+    }
+    if cfg.n_shared:
+        rate["shared_ffn_TFLOPs"] = 2.0 * (n_up + 1) * T * H * F * cfg.n_shared / (stage_ms["shared_ffn"] * 1e-3) / 1e12
+    achieved = flops_gemm1 / (gemm_ms[1] * 1e-3) / 1e12
+    roof = {"kernel": "gemm_bf16_kernel<%s> (first FFN GEMM with the activation)" % {0: "SiLU", 1: "GELU", 2: "SwiGLU"}[cfg.act],
+            "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+            "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None, "launch_ms": float(gemm_ms[1]),
+            "flops_per_launch": flops_gemm1}
+    return stage_ms, rate, roof
+
+
+def config_of(cfg, wl, share):
+    return {"workload": cfg.name, "T": cfg.T, "H": cfg.H, "F": cfg.F, "E": cfg.E, "k": cfg.k, "G": cfg.G,
+            "received_rows": wl["R"], "gpu_under_test": wl["g"], "share": share, "act": cfg.act,
+            "shared_experts": cfg.n_shared}
+
+
+def run_single(args, torch, P, W):
+    cfg = W.get_config(args.workload)
+    wl = build_workload(cfg, torch, P, W, args.share)
+    ms_per_step, wall_ms, launch = measure_step(torch, wl["step"], [wl["y"]], args)
+    stage_ms, rate, roof = measure_stages(torch, wl, cfg, max(3, args.steps // 2))
+    if args.share == "bottleneck":
+        roof["traffic"] = gemm1_traffic_bytes(cfg.name)
+    line = {
+        "metric": "MoE-layer tokens/sec on 1 MI355X", "value": cfg.T / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": config_of(cfg, wl, args.share),
+        "wall_ms_per_step": wall_ms, "launch": launch,
+        "stage_ms": {n: round(v, 4) for n, v in stage_ms.items()}, "stage_rate": rate, "roofline": roof,
+    }
+    line["paper_model"] = paper_model(cfg, wl, stage_ms, P)
+    line["box_reference"] = box_reference(torch, wl, cfg, P)
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline_line([(cfg, wl)], W)
+    return line
+
+
+def build_coloc(torch, P, W):
+    """The colocated GPU of Sec. 6: model a (8 experts, one per GPU) and model b (16 experts, two per GPU) on
+    the same 8 GPUs.  colocate_match pairs a's expert p with the block of b's experts that lives on one GPU
+    (Sec. 6.2 Case II on the two 8 x 8 traffic matrices), so GPU p hosts a's expert p and b's block pair[p];
+    the GPU under test is the one that receives most rows of both models together."""
+    ca, cb = W.get_config("c4a_coloc"), W.get_config("c4b_coloc")
+    Da, Db = W.make_traffic_matrix(ca)["D"], W.make_traffic_matrix(cb)["D"]
+    pair, bott = P.colocate_match(Da, Db)
+    pair = [int(v) for v in pair]
+    Dn = Da + Db[np.ix_(pair, pair)]
+    g = int(np.argmax(Dn.sum(axis=0)))
+    wa = build_workload(ca, torch, P, W, placement=(g, list(range(ca.G))))
+    wb = build_workload(cb, torch, P, W, placement=(g, pair))
+    side = torch.cuda.Stream()                               # default priority
+
+    def ffn_two_streams():
+        main_s = torch.cuda.current_stream()
+        side.wait_stream(main_s)
+        wa["ffn"]()
+        with torch.cuda.stream(side):
+            wb["ffn"]()
+        main_s.wait_stream(side)
+
+    def ffn_serial():
+        wa["ffn"]()
+        wb["ffn"]()
+
+    def step_with(ffn):
+        def step():
+            wa["front"]()
+            wb["front"]()
+            ffn()
+            wa["back"]()
+            wb["back"]()
+        return step
+
+    return dict(ca=ca, cb=cb, wa=wa, wb=wb, pair=pair, bottleneck=float(bott), g=g, Dn=Dn,
+                ffn_two_streams=ffn_two_streams, ffn_serial=ffn_serial, step=step_with(ffn_two_streams),
+                step_serial=step_with(ffn_serial), keep=side)
+
+
+def run_coloc(args, torch, P, W):
+    co = build_coloc(torch, P, W)
+    ca, cb, wa, wb = co["ca"], co["cb"], co["wa"], co["wb"]
+    ms_per_step, wall_ms, launch = measure_step(torch, co["step"], [wa["y"], wb["y"]], args)
+    reps = max(3, args.steps // 2)
+    ms_serial = time_graph(torch, capture(torch, co["step_serial"]), reps, 1)
+    ffn_two = time_graph(torch, capture(torch, co["ffn_two_streams"]), reps, 1)
+    ffn_ser = time_graph(torch, capture(torch, co["ffn_serial"]), reps, 1)
+    sa, ra, roof = measure_stages(torch, wa, ca, reps)
+    sb, rb, _ = measure_stages(torch, wb, cb, reps)
+    line = {
+        "metric": "MoE-layer tokens/sec on 1 MI355X", "value": (ca.T + cb.T) / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": ca.dtype, "data": "synthetic",
+        "config": {"workload": "c4_coloc", "model_a": config_of(ca, wa, "colocated"), "model_b": config_of(cb, wb, "colocated"),
+                   "pair": co["pair"], "bottleneck_weight": co["bottleneck"], "gpu_under_test": co["g"],
+                   "step": "both models' gate/traffic/dispatch, the two expert FFNs on two HIP streams, both combines"},
+        "wall_ms_per_step": wall_ms, "launch": launch,
+        "coloc": {"step_two_streams_ms": ms_per_step, "step_one_stream_ms": ms_serial,
+                  "ffn_two_streams_ms": ffn_two, "ffn_one_stream_ms": ffn_ser},
+        "stage_ms": {"model_a": {n: round(v, 4) for n, v in sa.items()}, "model_b": {n: round(v, 4) for n, v in sb.items()}},
+        "stage_rate": {"model_a": ra, "model_b": rb}, "roofline": roof,
+    }
+    line["box_reference"] = box_reference(torch, wa, ca, P)
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline_line([(ca, wa), (cb, wb)], W)
+    return line
 
 
 def main():
@@ -299,7 +585,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c2_mixtral")
+    ap.add_argument("--workload", default="c2_mixtral",
+                    help="c2_mixtral (default), c1_tiny_fp32, c3_switch, c4a_coloc, c4b_coloc, c5_finegrained, or "
+                         "c4_coloc: both colocated models on the GPU that colocate_match gives them")
     ap.add_argument("--share", choices=["bottleneck", "median"], default="bottleneck",
                     help="which GPU's share to run: the one that receives most rows (sets the layer time) or the median one")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -318,84 +606,7 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs the MI355X (no CPU fallback exists)", file=sys.stderr)
         sys.exit(2)
-    cfg = W.get_config(args.workload)
-    wl = build_workload(cfg, torch, P, W, args.share)
-    step = wl["step"]
-
-    # The step is recorded once into a HIP graph (no memset nodes: the library clears nothing with
-    # hipMemsetAsync) and replayed; replays are checked against the eager result before timing.
-    step()
-    torch.cuda.synchronize()
-    y_eager = wl["y"].clone()
-    use_graph = not args.no_graph
-    if use_graph:
-        g_step = capture(torch, step)
-        for _ in range(3):
-            wl["y"].zero_()
-            g_step.replay()
-            torch.cuda.synchronize()
-            if not torch.equal(wl["y"], y_eager):
-                print("graph replay differs from the eager step", file=sys.stderr)
-                sys.exit(3)
-        run_step = g_step.replay
-    else:
-        run_step = step
-    for _ in range(args.warmup):
-        run_step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    a.record()
-    for _ in range(args.steps):
-        run_step()
-    b.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    ms_per_step = a.elapsed_time(b) / args.steps
-
-    reps = max(3, args.steps // 2)
-    stage_ms = {}
-    for name, fn in wl["stages"].items():                   # GPU time of each stage: 10 calls per graph replay
-        per = 10 if name != "expert_ffn" else 1
-        stage_ms[name] = time_graph(torch, capture(torch, fn, per), reps, per)
-    stage_ms["dispatch"] = stage_ms.pop("traffic+dispatch") - stage_ms["traffic"]
-    stage_ms["dispatch_chunks (not in the step)"] = stage_ms.pop("traffic+dispatch_chunks") - stage_ms["traffic"]
-    gemm_ms = np.mean([wl["ffn_timed"]() for _ in range(reps)], axis=0)   # tile map, GEMM1 (+act), GEMM2
-
-    R, T, k, H, F, b_el = wl["R"], cfg.T, cfg.k, cfg.H, cfg.F, (2 if cfg.dtype == "bf16" else 4)
-    n_up = 2 if cfg.act == 2 else 1
-    flops_gemm1 = 2.0 * n_up * R * H * F
-    flops_gemm2 = 2.0 * R * H * F
-    achieved = flops_gemm1 / (gemm_ms[1] * 1e-3) / 1e12
-    bytes_dispatch = T * H * b_el + wl["n_kept"] * H * b_el + T * k * 12
-    bytes_combine = wl["n_kept"] * H * b_el + T * H * b_el + T * k * 8
-    bytes_route = T * H * b_el + cfg.E * H * b_el + T * k * 8
-    line = {
-        "metric": "MoE-layer tokens/sec on 1 MI355X", "value": T / (ms_per_step * 1e-3), "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
-        "config": {"workload": cfg.name, "T": T, "H": H, "F": F, "E": cfg.E, "k": k, "G": cfg.G,
-                   "received_rows": R, "gpu_under_test": wl["g"], "share": args.share, "act": cfg.act},
-        "wall_ms_per_step": wall_ms, "launch": "hip graph replay" if use_graph else "eager",
-        "stage_ms": {n: round(v, 4) for n, v in stage_ms.items()},
-        "stage_rate": {
-            "route_GBps": bytes_route / (stage_ms["route"] * 1e-3) / 1e9,
-            "dispatch_GBps": bytes_dispatch / (stage_ms["dispatch"] * 1e-3) / 1e9,
-            "combine_GBps": bytes_combine / (stage_ms["combine"] * 1e-3) / 1e9,
-            "ffn_TFLOPs": (flops_gemm1 + flops_gemm2) / (stage_ms["expert_ffn"] * 1e-3) / 1e12,
-            "ffn_mfma_util": (flops_gemm1 + flops_gemm2) / (stage_ms["expert_ffn"] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-            "gemm2_TFLOPs": flops_gemm2 / (gemm_ms[2] * 1e-3) / 1e12,
-            "tilemap_ms": float(gemm_ms[0]),
-        },
-        "roofline": {"kernel": "gemm_bf16_kernel<SwiGLU> (first FFN GEMM with the activation)", "bound": "mfma",
-                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": GEMM1_TRAFFIC_BYTES.get(cfg.name) if args.share == "bottleneck" else None,
-                     "launch_ms": float(gemm_ms[1]), "flops_per_launch": flops_gemm1},
-    }
-    line["paper_model"] = paper_model(cfg, wl, stage_ms, P)
-    line["box_reference"] = box_reference(torch, wl, cfg)
-    if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(cfg, wl, W)
+    line = run_coloc(args, torch, P, W) if args.workload == "c4_coloc" else run_single(args, torch, P, W)
     print(json.dumps(line))
 
 

@@ -254,6 +254,20 @@ int moe_selfcheck_tile_order(int32_t tiles_m, int32_t tiles_n, int32_t ncu, int3
 int moe_selfcheck_tile_map(const int32_t* seg_offset, const int32_t* seg_expert, int32_t nseg, int32_t R, int32_t bm,
                            int32_t n_local, int32_t gather);
 
+/* Reference measurements of the device (used by bench.py's box_reference; both record HIP events on `stream`
+ * around their one kernel, WAIT for it and return its duration in milliseconds in ms_out, HOST [1]).
+ *
+ * moe_diag_mfma_only: n_blocks blocks of 4 waves, every wave issues iters x 16 independent
+ * v_mfma_f32_32x32x16_bf16 (the FFN kernel's 4 x 4 register blocking) on operands that stay in registers: what
+ * the matrix cores sustain with no operand traffic at all.  sink: device [n_blocks*256] fp32 out (sums, so
+ * that the work cannot be dropped).  flop_out HOST [1]: the floating-point operations issued.
+ * iters a multiple of 4 in [4, 2^24], 1 <= n_blocks <= 65536.
+ *
+ * moe_diag_copy_1r2w: dst0 = dst1 = src, `bytes` (a multiple of 16) read once and written twice with 16-byte
+ * streaming accesses: the traffic shape of a top-2 send buffer without any indexing. */
+int moe_diag_mfma_only(int32_t n_blocks, int32_t iters, float* sink, void* stream, float* ms_out, double* flop_out);
+int moe_diag_copy_1r2w(const void* src, void* dst0, void* dst1, size_t bytes, void* stream, float* ms_out);
+
 /* ------------------------------------------------------------------ host planners */
 
 /* Result of aurora_order; arrays are owned by the library until

@@ -245,6 +245,23 @@ def moe_combine(ctx, ret, slot_to_row, topk_w, shared_out, y):
                                               _ptr(shared_out), _ptr(y), _stream()))
 
 
+def moe_diag_mfma_only(n_blocks, iters, sink):
+    """Register-only MFMA loop; returns (milliseconds, floating-point operations issued).  Synchronises."""
+    ms, flop = C.c_float(), C.c_double()
+    _check("moe_diag_mfma_only", _lib.load().moe_diag_mfma_only(n_blocks, iters, _ptr(sink), _stream(), C.byref(ms),
+                                                                 C.byref(flop)))
+    return ms.value, flop.value
+
+
+def moe_diag_copy_1r2w(src, dst0, dst1):
+    """dst0 = dst1 = src with streaming 16-byte accesses; returns milliseconds.  Synchronises."""
+    ms = C.c_float()
+    nbytes = src.numel() * src.element_size()
+    _check("moe_diag_copy_1r2w", _lib.load().moe_diag_copy_1r2w(_ptr(src), _ptr(dst0), _ptr(dst1), nbytes, _stream(),
+                                                                 C.byref(ms)))
+    return ms.value
+
+
 # ------------------------------------------------------------------ host planners (no GPU needed)
 def _i64_matrix(D):
     a = np.ascontiguousarray(D, dtype=np.int64)

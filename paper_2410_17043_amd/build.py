@@ -13,7 +13,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libaurora_moe.so")
-SOURCES = ["status.cpp", "host_plan.cpp", "route.hip", "dispatch.hip", "combine.hip", "ffn.hip"]
+SOURCES = ["status.cpp", "host_plan.cpp", "route.hip", "dispatch.hip", "combine.hip", "ffn.hip", "diag.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-ffp-contract=off"]
@@ -38,7 +38,7 @@ def build(verbose: bool = False, extra_flags=()) -> str:
             print(out)
         return obj
 
-    with ThreadPoolExecutor(max_workers=min(6, os.cpu_count() or 1)) as ex:
+    with ThreadPoolExecutor(max_workers=min(7, os.cpu_count() or 1)) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     _run([hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB, *objs])
     return LIB

@@ -77,6 +77,30 @@ def rel_err(got, ref):
     return float(np.max(np.abs(np.asarray(got, dtype=np.float64) - ref)) / max(np.max(np.abs(ref)), 1e-300))
 
 
+def rms_rel_err(got, ref):
+    """Root-mean-square error over the root-mean-square of the reference: unlike the normwise error it is not
+    set by the few largest elements, so small elements that are wrong by a large factor show."""
+    ref = np.asarray(ref, dtype=np.float64)
+    diff = np.asarray(got, dtype=np.float64) - ref
+    return float(np.sqrt(np.mean(diff * diff)) / max(np.sqrt(np.mean(ref * ref)), 1e-300))
+
+
+# FFN and layer outputs: the normwise bound is the stated tolerance (1e-5 fp32, 2e-2 bf16).  The RMS bound
+# follows from the arithmetic: a bf16 result is rounded once at the intermediate and once at the output, each
+# a relative error of at most 2^-9 spread evenly (RMS 2^-9 / sqrt(3) = 1.1e-3 each, 1.6e-3 together, plus
+# the fast exp/reciprocal of the activation), so 5e-3 leaves a factor of three; fp32 sums of at most a few
+# hundred products in another order than the fp64 reference stay below 1e-6.
+TOL = {"fp32": 1e-5, "bf16": 2e-2}
+RMS_TOL = {"fp32": 1e-6, "bf16": 5e-3}
+
+
+def assert_close(got, ref, dtype, what=""):
+    """Both bounds; returns (normwise, rms)."""
+    e, r = rel_err(got, ref), rms_rel_err(got, ref)
+    assert e < TOL[dtype] and r < RMS_TOL[dtype], (what, e, r)
+    return e, r
+
+
 def run_emulated_cluster(cfg, dest_orders=None, n_shared=0, chunked=False):
     """The whole layer over cfg.G simulated GPUs on the one real GPU.
 

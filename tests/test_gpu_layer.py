@@ -25,9 +25,8 @@ def check_cluster(H, cfg, n_shared=0, chunked=False):
     for g in range(cfg.G):
         ref = O.layer_dense(res["inputs"][g]["x"], inp0["w_gate"], inp0["gate_bias"], cfg.k, cfg.renorm,
                             res["experts"], cfg.act, cfg.capacity, res["shared"] or None)
-        err = H.rel_err(res["y"][g], ref)
+        err, _rms = H.assert_close(res["y"][g], ref, cfg.dtype, g)
         worst = max(worst, err)
-        assert err < TOL[cfg.dtype], (g, err)
     # the measured traffic matrix is what the oracle counts
     for g in range(cfg.G):
         idx, _, _ = O.route(res["inputs"][g]["x"], inp0["w_gate"], inp0["gate_bias"], cfg.k, cfg.renorm)
@@ -90,11 +89,16 @@ def test_two_colocated_models_concurrent_streams_match_serial(H):
     streams = {k: torch.cuda.Stream() for k in cases}            # default priority
     for rep in range(3):
         for k in cases:
+            conc[k].zero_()
+        for k in cases:
+            streams[k].wait_stream(torch.cuda.current_stream())  # the zero fill above is ordered before the FFN
             with torch.cuda.stream(streams[k]):
                 launch(k, conc[k])
+        for k in cases:
+            torch.cuda.current_stream().wait_stream(streams[k])
         torch.cuda.synchronize()
         for k in cases:
             assert torch.equal(conc[k], serial[k])
     for k, (cfg, R, recv, w, *_rest) in data.items():
         ref = O.ffn(H.host(recv), H.host(w["w1"]), H.host(w["w_up"]), H.host(w["w_down"]), cfg.act)
-        assert H.rel_err(H.host(serial[k]), ref) < TOL["bf16"]
+        H.assert_close(H.host(serial[k]), ref, "bf16", k)
