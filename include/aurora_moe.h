@@ -264,9 +264,10 @@ int moe_selfcheck_tile_map(const int32_t* seg_offset, const int32_t* seg_expert,
  * iters a multiple of 4 in [4, 2^24], 1 <= n_blocks <= 65536.
  *
  * moe_diag_copy_1r2w: dst0 = dst1 = src, `bytes` (a multiple of 16) read once and written twice with 16-byte
- * streaming accesses: the traffic shape of a top-2 send buffer without any indexing. */
+ * accesses, a wave per 8 KB: the traffic shape of a top-2 send buffer without any indexing.  The kernel is
+ * launched `reps` times (1..1000) back to back between the two events; ms_out is the average per launch. */
 int moe_diag_mfma_only(int32_t n_blocks, int32_t iters, float* sink, void* stream, float* ms_out, double* flop_out);
-int moe_diag_copy_1r2w(const void* src, void* dst0, void* dst1, size_t bytes, void* stream, float* ms_out);
+int moe_diag_copy_1r2w(const void* src, void* dst0, void* dst1, size_t bytes, int32_t reps, void* stream, float* ms_out);
 
 /* ------------------------------------------------------------------ host planners */
 

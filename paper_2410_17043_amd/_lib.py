@@ -53,7 +53,7 @@ SIGNATURES = {
                                        _vp, _vp, _sz, _vp, C.POINTER(C.c_float)]),
     "moe_combine": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "moe_diag_mfma_only": (C.c_int, [_i32, _i32, _vp, _vp, C.POINTER(C.c_float), C.POINTER(C.c_double)]),
-    "moe_diag_copy_1r2w": (C.c_int, [_vp, _vp, _vp, _sz, _vp, C.POINTER(C.c_float)]),
+    "moe_diag_copy_1r2w": (C.c_int, [_vp, _vp, _vp, _sz, _i32, _vp, C.POINTER(C.c_float)]),
     "moe_selfcheck_tile_order": (C.c_int, [_i32, _i32, _i32, _i32]),
     "moe_selfcheck_tile_map": (C.c_int, [_pi32, _pi32, _i32, _i32, _i32, _i32, _i32]),
     "aurora_order": (C.c_int, [_i32, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(aurora_schedule)]),

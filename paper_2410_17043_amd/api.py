@@ -253,11 +253,11 @@ def moe_diag_mfma_only(n_blocks, iters, sink):
     return ms.value, flop.value
 
 
-def moe_diag_copy_1r2w(src, dst0, dst1):
-    """dst0 = dst1 = src with streaming 16-byte accesses; returns milliseconds.  Synchronises."""
+def moe_diag_copy_1r2w(src, dst0, dst1, reps=1):
+    """dst0 = dst1 = src, `reps` launches back to back; returns milliseconds per launch.  Synchronises."""
     ms = C.c_float()
     nbytes = src.numel() * src.element_size()
-    _check("moe_diag_copy_1r2w", _lib.load().moe_diag_copy_1r2w(_ptr(src), _ptr(dst0), _ptr(dst1), nbytes, _stream(),
+    _check("moe_diag_copy_1r2w", _lib.load().moe_diag_copy_1r2w(_ptr(src), _ptr(dst0), _ptr(dst1), nbytes, reps, _stream(),
                                                                  C.byref(ms)))
     return ms.value
 

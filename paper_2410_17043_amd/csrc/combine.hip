@@ -3,8 +3,9 @@
 // `ret` is in send-buffer row order (the second all-to-all is the reverse of the
 // first with the same sizes, Sec. 2.2).  One wave per token: the k source rows are
 // gathered with 16-byte lanes (1 KB per wave access), accumulated in fp32 in slot
-// order j = 0..k-1 and rounded once on the way out.  Pure streaming: every input
-// row is read exactly once, every output row written once.
+// order j = 0..k-1 and rounded once on the way out.  Every input row is read exactly
+// once (plain loads while the rows fit the memory-side cache, streaming loads beyond,
+// see kCombineCacheableBytes); the output goes out with streaming stores.
 #include "common.h"
 
 namespace {
@@ -37,7 +38,7 @@ template <> struct Pack<MOE_F32> {
     }
 };
 
-template <int DT, int K>
+template <int DT, int K, bool STREAM>
 __global__ __launch_bounds__(256) void combine_kernel(const u32x4* __restrict__ ret, const int32_t* __restrict__ slot_to_row,
                                                       const float* __restrict__ topk_w, const u32x4* __restrict__ shared_out,
                                                       int T, int k_rt, int row16, u32x4* __restrict__ y) {
@@ -54,18 +55,22 @@ __global__ __launch_bounds__(256) void combine_kernel(const u32x4* __restrict__ 
         rows[j] = (j < k) ? slot_to_row[(size_t)t * k + j] : -1;
         w[j] = (j < k) ? topk_w[(size_t)t * k + j] : 0.f;
     }
-    // two 16-byte chunks per lane per trip: 2k independent row loads in flight before the first use
-    for (int c0 = lane; c0 < row16; c0 += 128) {
-        u32x4 q[2][KM];
+    // CPT 16-byte chunks per lane per trip, about eight independent row loads in flight before the first use
+    constexpr int CPT = (K > 0 && K < 4) ? 8 / K : 2;
+    for (int c0 = lane; c0 < row16; c0 += 64 * CPT) {
+        u32x4 q[CPT][KM];
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+        for (int u = 0; u < CPT; ++u) {
             const int c = c0 + 64 * u;
 #pragma unroll
             for (int j = 0; j < KM; ++j)
-                if (c < row16 && rows[j] >= 0) q[u][j] = __builtin_nontemporal_load(ret + (size_t)rows[j] * row16 + c);
+                if (c < row16 && rows[j] >= 0) {
+                    const u32x4* p = ret + (size_t)rows[j] * row16 + c;
+                    q[u][j] = STREAM ? __builtin_nontemporal_load(p) : *p;
+                }
         }
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+        for (int u = 0; u < CPT; ++u) {
             const int c = c0 + 64 * u;
             if (c >= row16) continue;
             float acc[V];
@@ -91,7 +96,12 @@ __global__ __launch_bounds__(256) void combine_kernel(const u32x4* __restrict__ 
     }
 }
 
-template <int DT>
+// Rows that were just written by the return transfer are still in the memory-side cache (256 MB) when they
+// are not too many: plain loads then (17 against 19 us at the Mixtral-shape share, 67 MB); beyond half of that
+// cache plain loads only evict each other (103 against 86 us at 403 MB) and streaming loads are used.
+constexpr size_t kCombineCacheableBytes = (size_t)128 << 20;
+
+template <int DT, bool STREAM>
 int launch_combine(const moe_ctx* c, const void* ret, const int32_t* s2r, const float* w, const void* shared, void* y,
                    hipStream_t st) {
     const moe_shape& s = c->s;
@@ -100,12 +110,21 @@ int launch_combine(const moe_ctx* c, const void* ret, const int32_t* s2r, const 
     const u32x4* r = reinterpret_cast<const u32x4*>(ret);
     const u32x4* sh = reinterpret_cast<const u32x4*>(shared);
     u32x4* yo = reinterpret_cast<u32x4*>(y);
-    if (s.k == 1) hipLaunchKernelGGL((combine_kernel<DT, 1>), grid, dim3(256), 0, st, r, s2r, w, sh, s.T, s.k, row16, yo);
-    else if (s.k == 2) hipLaunchKernelGGL((combine_kernel<DT, 2>), grid, dim3(256), 0, st, r, s2r, w, sh, s.T, s.k, row16, yo);
-    else if (s.k <= 8 && s.k == 6) hipLaunchKernelGGL((combine_kernel<DT, 6>), grid, dim3(256), 0, st, r, s2r, w, sh, s.T, s.k, row16, yo);
-    else hipLaunchKernelGGL((combine_kernel<DT, 0>), grid, dim3(256), 0, st, r, s2r, w, sh, s.T, s.k, row16, yo);
+    if (s.k == 1) hipLaunchKernelGGL((combine_kernel<DT, 1, STREAM>), grid, dim3(256), 0, st, r, s2r, w, sh, s.T, s.k, row16, yo);
+    else if (s.k == 2) hipLaunchKernelGGL((combine_kernel<DT, 2, STREAM>), grid, dim3(256), 0, st, r, s2r, w, sh, s.T, s.k, row16, yo);
+    else if (s.k == 6) hipLaunchKernelGGL((combine_kernel<DT, 6, STREAM>), grid, dim3(256), 0, st, r, s2r, w, sh, s.T, s.k, row16, yo);
+    else hipLaunchKernelGGL((combine_kernel<DT, 0, STREAM>), grid, dim3(256), 0, st, r, s2r, w, sh, s.T, s.k, row16, yo);
     MOE_LAUNCH_CHECK("combine_kernel");
     return MOE_OK;
+}
+
+template <int DT>
+int launch_combine_dt(const moe_ctx* c, const void* ret, const int32_t* s2r, const float* w, const void* shared, void* y,
+                      hipStream_t st) {
+    const moe_shape& s = c->s;
+    const size_t bytes = (size_t)s.T * s.k * s.H * elem_size(s.dtype);
+    if (bytes > kCombineCacheableBytes) return launch_combine<DT, true>(c, ret, s2r, w, shared, y, st);
+    return launch_combine<DT, false>(c, ret, s2r, w, shared, y, st);
 }
 
 }  // namespace
@@ -116,6 +135,6 @@ extern "C" int moe_combine(moe_ctx* ctx, const void* ret, const int32_t* slot_to
     if (!aligned16(ret) || !aligned16(y) || !aligned16(shared_out))
         return moe_set_error(MOE_EALIGN, "moe_combine: ret, y and shared_out must be 16-byte aligned");
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    if (ctx->s.dtype == MOE_BF16) return launch_combine<MOE_BF16>(ctx, ret, slot_to_row, topk_w, shared_out, y, st);
-    return launch_combine<MOE_F32>(ctx, ret, slot_to_row, topk_w, shared_out, y, st);
+    if (ctx->s.dtype == MOE_BF16) return launch_combine_dt<MOE_BF16>(ctx, ret, slot_to_row, topk_w, shared_out, y, st);
+    return launch_combine_dt<MOE_F32>(ctx, ret, slot_to_row, topk_w, shared_out, y, st);
 }

@@ -17,7 +17,8 @@
 // per-expert totals into segment starts for the requested destination order (a 256-wide
 // prefix sum), then each wave computes the send rows of its token's slots from the cached
 // ranks, writes slot_to_row / row_to_slot, reads the token row once and writes it to the
-// rows of its kept slots (16-byte lanes, 1 KB per wave access, streaming loads/stores).
+// rows of its kept slots (16-byte lanes, 1 KB per wave access, a whole 8 KB row in flight per wave,
+//   cacheable loads - the gate has just read x - and streaming stores).
 #include "common.h"
 #include <algorithm>
 #include <mutex>
@@ -29,7 +30,6 @@ namespace {
 struct SegMap {                       // built on the host from expert_to_gpu and dest_order
     int16_t seg_expert[MOE_MAX_E];    // expert at each position of the send order
     uint8_t expert_gpu[MOE_MAX_E];    // destination GPU of each expert
-    uint8_t expert_pos[MOE_MAX_E];    // position of each expert in the send order (inverse of seg_expert)
 };
 
 constexpr int kChunks = MOE_SLOTS_PER_BLOCK / 64;   // 16 chunks of 64 slots per block, in slot order
@@ -270,21 +270,22 @@ __global__ __launch_bounds__(1024) void small_rank_kernel(const int32_t* __restr
     traffic_outputs(raw, kept, E, G, capacity, map, expert_count, dest_count, n_dropped);
 }
 
-// Writes the token row at `src` (its first 4 KB already requested into v) to the send rows of the
+// Writes the token row at `src` (its first 8 KB already requested into v) to the send rows of the
 // token's k slots; lane j < k holds the row of slot j in my_row (-1: dropped).
+constexpr int kRowLoads = 8;          // 16-byte loads in flight per lane: a whole 8 KB row per wave
 template <int K>
-__device__ __forceinline__ void copy_token_rows(const u32x4* __restrict__ src, u32x4 (&v)[4], int my_row, int k, int row16,
+__device__ __forceinline__ void copy_token_rows(const u32x4* __restrict__ src, u32x4 (&v)[kRowLoads], int my_row, int k, int row16,
                                                 u32x4* __restrict__ send_buf, int lane) {
     constexpr int KM = (K > 0) ? K : MOE_MAX_K;
     int rows[KM];
 #pragma unroll
     for (int j = 0; j < KM; ++j) rows[j] = (j < k) ? __shfl(my_row, j, 64) : -1;
-    for (int c0 = 0; c0 < row16; c0 += 256) {
+    for (int c0 = 0; c0 < row16; c0 += 64 * kRowLoads) {
         if (c0 > 0) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < kRowLoads; ++u) {
                 const int c = c0 + u * 64 + lane;
-                if (c < row16) v[u] = __builtin_nontemporal_load(src + c);
+                if (c < row16) v[u] = src[c];
             }
         }
 #pragma unroll
@@ -292,7 +293,7 @@ __device__ __forceinline__ void copy_token_rows(const u32x4* __restrict__ src, u
             if (rows[j] >= 0) {
                 u32x4* dst = send_buf + (size_t)rows[j] * row16;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < kRowLoads; ++u) {
                     const int c = c0 + u * 64 + lane;
                     if (c < row16) __builtin_nontemporal_store(v[u], dst + c);
                 }
@@ -309,26 +310,41 @@ __global__ __launch_bounds__(256) void scatter_kernel(const u32x4* __restrict__ 
                                                       int capacity, SegMap map, int row16, u32x4* __restrict__ send_buf,
                                                       int32_t* __restrict__ slot_to_row, int32_t* __restrict__ row_to_slot,
                                                       int32_t* __restrict__ seg_offset, int32_t* __restrict__ seg_expert) {
-    __shared__ int seg_first[MOE_MAX_E];   // first send row of each expert
+    __shared__ int seg_first[MOE_MAX_E];   // E > 64: first send row of each expert
+    __shared__ int cnt_of[MOE_MAX_E];      // E > 64: total of each expert
+    __shared__ int wave_first[4][64];      // E <= 64: first send row of each expert, one copy per wave
     __shared__ int wave_sum[4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int t = blockIdx.x * 4 + wave;
     const int k = (K > 0) ? K : k_rt;
     const bool live = t < T;
     const u32x4* src = x + (size_t)(live ? t : 0) * row16;
-    // the first 4 KB of the row are requested before anything else: they do not depend on the ranks
-    u32x4 v[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int c = u * 64 + lane;
-        if (live && c < row16) v[u] = __builtin_nontemporal_load(src + c);
+    // Memory returns a wave's loads in the order they were issued, so the small loads that the send rows
+    // depend on go out first (all independent of each other: one round trip), then the 8 KB of the token row;
+    // the rows are worked out while the row data is still in flight.
+    int slot_e = -1, slot_rank_v = -1;
+    if (live && lane < k) {
+        slot_e = idx[t * k + lane];
+        slot_rank_v = slot_rank[t * k + lane];
     }
-    // Segment starts in send order.  Up to 64 experts every wave does the prefix sum for itself in
-    // registers (lane p = position p; no barrier, no LDS); beyond, the block shares one through LDS.
-    int excl_reg = 0;                                       // E <= 64: start of the segment at position `lane`
+    const int p_blk = (E <= 64) ? lane : threadIdx.x;       // send-order position this thread looks after
+    const int ex = (p_blk < E) ? map.seg_expert[p_blk] : 0;
+    int cnt_by_id = (p_blk < E) ? raw_count[p_blk] : 0;     // total of expert p_blk; the one of `ex` comes by shuffle / LDS
+    __builtin_amdgcn_sched_barrier(0);
+    // plain (cacheable) loads: the gate has just read x, so the rows come from the memory-side cache; the
+    // send rows are written with streaming stores
+    u32x4 v[kRowLoads];
+#pragma unroll
+    for (int u = 0; u < kRowLoads; ++u) {
+        const int c = u * 64 + lane;
+        if (live && c < row16) v[u] = src[c];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // Segment starts in send order.  Up to 64 experts every wave does the prefix sum for itself (lane p =
+    // position p, no block barrier); beyond, the block shares one through LDS.
     if (E <= 64) {
-        const int ex = (lane < E) ? map.seg_expert[lane] : 0;
-        int cnt = (lane < E) ? raw_count[ex] : 0;
+        int cnt = __shfl(cnt_by_id, ex, 64);
+        if (lane >= E) cnt = 0;
         if (capacity > 0 && cnt > capacity) cnt = capacity;
         int incl = cnt;
 #pragma unroll
@@ -336,16 +352,20 @@ __global__ __launch_bounds__(256) void scatter_kernel(const u32x4* __restrict__ 
             const int up = __shfl_up(incl, o, 64);
             if (lane >= o) incl += up;
         }
-        excl_reg = incl - cnt;
+        const int excl = incl - cnt;
+        if (lane < E) wave_first[wave][ex] = excl;
         if (blockIdx.x == 0 && wave == 0 && lane < E) {
-            seg_offset[lane] = excl_reg;
+            seg_offset[lane] = excl;
             seg_expert[lane] = ex;
             if (lane == E - 1) seg_offset[E] = incl;
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");     // a wave reads back only what it wrote itself
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     } else {
-        const int p = threadIdx.x;
-        const int ex = (p < E) ? map.seg_expert[p] : 0;
-        int cnt = (p < E) ? raw_count[ex] : 0;
+        if (p_blk < E) cnt_of[p_blk] = cnt_by_id;
+        __syncthreads();
+        int cnt = (p_blk < E) ? cnt_of[ex] : 0;
         if (capacity > 0 && cnt > capacity) cnt = capacity;
         int incl = cnt;                                     // inclusive scan inside the wave
 #pragma unroll
@@ -360,33 +380,24 @@ __global__ __launch_bounds__(256) void scatter_kernel(const u32x4* __restrict__ 
         for (int w = 0; w < 4; ++w)
             if (w < wave) before += wave_sum[w];
         const int excl = before + incl - cnt;
-        if (p < E) {
+        if (p_blk < E) {
             seg_first[ex] = excl;
             if (blockIdx.x == 0) {
-                seg_offset[p] = excl;
-                seg_expert[p] = ex;
-                if (p == E - 1) seg_offset[E] = excl + cnt;
+                seg_offset[p_blk] = excl;
+                seg_expert[p_blk] = ex;
+                if (p_blk == E - 1) seg_offset[E] = excl + cnt;
             }
         }
         __syncthreads();
     }
     if (!live) return;
     // send rows of this token's slots: lane j < k works out slot j, then all lanes learn the k rows
-    int my_row = -1, my_e = 0, my_rank = 0;
-    bool kept_slot = false;
+    int my_row = -1;
     if (lane < k) {
         const int s = t * k + lane;
-        const int e = idx[s], rank = slot_rank[s];
-        kept_slot = e >= 0 && e < E && rank >= 0 && (capacity <= 0 || rank < capacity);
-        my_e = kept_slot ? e : 0;
-        my_rank = rank;
-    }
-    // position of an expert in the send order: map.expert_pos is the inverse of map.seg_expert
-    const int first = (E <= 64) ? __shfl(excl_reg, map.expert_pos[my_e], 64) : seg_first[my_e];
-    if (lane < k) {
-        const int s = t * k + lane;
-        if (kept_slot) {
-            my_row = first + my_rank;
+        const int e = slot_e, rank = slot_rank_v;
+        if (e >= 0 && e < E && rank >= 0 && (capacity <= 0 || rank < capacity)) {
+            my_row = ((E <= 64) ? wave_first[wave][e] : seg_first[e]) + rank;
             row_to_slot[my_row] = s;
         }
         slot_to_row[s] = my_row;
@@ -540,11 +551,11 @@ __global__ __launch_bounds__(256) void scatter_chunks_kernel(const u32x4* __rest
     const int k = (K > 0) ? K : k_rt;
     if (t >= T) return;
     const u32x4* src = x + (size_t)t * row16;
-    u32x4 v[4];
+    u32x4 v[kRowLoads];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < kRowLoads; ++u) {
         const int c = u * 64 + lane;
-        if (c < row16) v[u] = __builtin_nontemporal_load(src + c);
+        if (c < row16) v[u] = src[c];
     }
     int my_row = -1;
     if (lane < k) {
@@ -580,10 +591,7 @@ int build_segmap(const moe_shape& s, const int32_t* expert_to_gpu, const int32_t
         if (d < 0 || d >= s.G || seen[d]) return moe_set_error(MOE_ESHAPE, "dest_order is not a permutation of 0..%d", s.G - 1);
         seen[d] = true;
         for (int e = 0; e < s.E; ++e)
-            if (expert_to_gpu[e] == d) {
-                m->expert_pos[e] = (uint8_t)p;
-                m->seg_expert[p++] = (int16_t)e;
-            }
+            if (expert_to_gpu[e] == d) m->seg_expert[p++] = (int16_t)e;
     }
     return MOE_OK;
 }
