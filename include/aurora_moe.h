@@ -266,6 +266,14 @@ int moe_selfcheck_tile_map(const int32_t* seg_offset, const int32_t* seg_expert,
  * moe_diag_copy_1r2w: dst0 = dst1 = src, `bytes` (a multiple of 16) read once and written twice with 16-byte
  * accesses, a wave per 8 KB: the traffic shape of a top-2 send buffer without any indexing.  The kernel is
  * launched `reps` times (1..1000) back to back between the two events; ms_out is the average per launch. */
+/* moe_diag_mfma_run_sum: what the gate's fast pass builds on, exposed so that a test can hold the hardware to
+ * the error model the gate assumes: d[t][i][j] = a chain of `run` v_mfma_f32_16x16x32_bf16, the first with a
+ * zero accumulator, i.e. the sum over k < 32 run of the exact products a[t][i][k] * b[t][j][k] as the matrix core
+ * forms and rounds it.
+ *   a, b  device [n_tiles][16][32 run] bf16 (16-byte aligned)    d  device [n_tiles][16][16] fp32 out
+ *   1 <= run <= 64.  Asynchronous on `stream` like the layer's entry points. */
+int moe_diag_mfma_run_sum(const void* a, const void* b, float* d, int32_t n_tiles, int32_t run, void* stream);
+
 int moe_diag_mfma_only(int32_t n_blocks, int32_t iters, float* sink, void* stream, float* ms_out, double* flop_out);
 int moe_diag_copy_1r2w(const void* src, void* dst0, void* dst1, size_t bytes, int32_t reps, void* stream, float* ms_out);
 

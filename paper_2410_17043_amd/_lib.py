@@ -52,6 +52,7 @@ SIGNATURES = {
     "moe_expert_ffn_timed": (C.c_int, [_vp, _i32, _vp, _vp, _i32, C.POINTER(moe_expert_w), _i32, _i32, _i32, _i32, _i32,
                                        _vp, _vp, _sz, _vp, C.POINTER(C.c_float)]),
     "moe_combine": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "moe_diag_mfma_run_sum": (C.c_int, [_vp, _vp, _vp, _i32, _i32, _vp]),
     "moe_diag_mfma_only": (C.c_int, [_i32, _i32, _vp, _vp, C.POINTER(C.c_float), C.POINTER(C.c_double)]),
     "moe_diag_copy_1r2w": (C.c_int, [_vp, _vp, _vp, _sz, _i32, _vp, C.POINTER(C.c_float)]),
     "moe_selfcheck_tile_order": (C.c_int, [_i32, _i32, _i32, _i32]),

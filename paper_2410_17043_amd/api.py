@@ -245,6 +245,12 @@ def moe_combine(ctx, ret, slot_to_row, topk_w, shared_out, y):
                                               _ptr(shared_out), _ptr(y), _stream()))
 
 
+def moe_diag_mfma_run_sum(a, b, d):
+    """d[t] = a chain of bf16 MFMAs (16x16x32, zero start) over a[t], b[t]; a, b [n,16,32*run] bf16, d [n,16,16] fp32."""
+    _check("moe_diag_mfma_run_sum", _lib.load().moe_diag_mfma_run_sum(_ptr(a), _ptr(b), _ptr(d), a.shape[0], a.shape[2] // 32,
+                                                                       _stream()))
+
+
 def moe_diag_mfma_only(n_blocks, iters, sink):
     """Register-only MFMA loop; returns (milliseconds, floating-point operations issued).  Synchronises."""
     ms, flop = C.c_float(), C.c_double()

@@ -74,6 +74,25 @@ __global__ __launch_bounds__(256) void copy_1r2w_kernel(const u32x4* __restrict_
         if (base + u * 64 < n16) __builtin_nontemporal_store(v[u], dst1 + base + u * 64);
 }
 
+// A chain of `run` v_mfma_f32_16x16x32_bf16 per 16 x 16 tile, the first with a zero accumulator:
+// d[t][i][j] = fp32 sum over k < 32 run of a[t][i][k] b[t][j][k] as the matrix core forms it, operands and result
+// in the lane layout the gate kernel uses (lane l: row l % 16, k = 8 (l / 16) .. + 7 of each 32; result rows
+// 4 (l / 16) + i, column l % 16).  One wave per tile.
+__global__ __launch_bounds__(64) void mfma_run_sum_kernel(const uint16_t* __restrict__ a, const uint16_t* __restrict__ b,
+                                                          int run, float* __restrict__ d) {
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    const int lane = threadIdx.x, r = lane & 15, g = lane >> 4;
+    const size_t t = blockIdx.x;
+    f32x4 out = {0.f, 0.f, 0.f, 0.f};
+    for (int q = 0; q < run; ++q) {
+        const bf16x8 av = *reinterpret_cast<const bf16x8*>(a + ((t * 16 + r) * run + q) * 32 + 8 * g);
+        const bf16x8 bv = *reinterpret_cast<const bf16x8*>(b + ((t * 16 + r) * run + q) * 32 + 8 * g);
+        out = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, bv, out, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) d[(t * 16 + 4 * g + i) * 16 + r] = out[i];
+}
+
 int timed(hipStream_t st, hipEvent_t* ev, float* ms_out) {
     MOE_HIP(hipEventSynchronize(ev[1]));
     MOE_HIP(hipEventElapsedTime(ms_out, ev[0], ev[1]));
@@ -134,4 +153,15 @@ extern "C" int moe_diag_copy_1r2w(const void* src, void* dst0, void* dst1, size_
     (void)hipEventDestroy(ev[0]);
     (void)hipEventDestroy(ev[1]);
     return rc;
+}
+
+extern "C" int moe_diag_mfma_run_sum(const void* a, const void* b, float* d, int32_t n_tiles, int32_t run, void* stream) {
+    if (!a || !b || !d) return moe_set_error(MOE_EINVAL, "moe_diag_mfma_run_sum: NULL argument");
+    if (n_tiles < 1 || n_tiles > (1 << 20) || run < 1 || run > 64)
+        return moe_set_error(MOE_ESHAPE, "moe_diag_mfma_run_sum: n_tiles must be in [1, 2^20] and run in [1, 64]");
+    if (!aligned16(a) || !aligned16(b)) return moe_set_error(MOE_EALIGN, "moe_diag_mfma_run_sum: 16-byte alignment needed");
+    hipLaunchKernelGGL(mfma_run_sum_kernel, dim3(n_tiles), dim3(64), 0, reinterpret_cast<hipStream_t>(stream),
+                       reinterpret_cast<const uint16_t*>(a), reinterpret_cast<const uint16_t*>(b), run, d);
+    MOE_LAUNCH_CHECK("mfma_run_sum_kernel");
+    return MOE_OK;
 }

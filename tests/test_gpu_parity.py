@@ -363,6 +363,41 @@ def test_expert_ffn_rows_beyond_the_32_bit_offsets_of_a_gathered_tile(H):
     H.assert_close(got, ref, "bf16")
 
 
+@pytest.mark.parametrize("run", [1, 2])
+def test_mfma_run_sum_stays_inside_the_error_model_of_the_gate(H, run):
+    """The gate certifies indices with the bound |run sum - exact| <= run * 1.05 * 2^-18 * sum |x_i w_i| on what
+    v_mfma_f32_16x16x32_bf16 returns.  The instruction is fed random and adversarial operands (wide exponent
+    spread, one huge term among many just too small to register, cancelling giants) and held to that bound;
+    the exact sums come from rationals-free fp64 (products of bf16 are exact, 64 of them add exactly enough)."""
+    r = np.random.default_rng(17 + run)
+    K = 32 * run
+    fam = []
+    a = r.standard_normal((512, 16, K)); b = 0.02 * r.standard_normal((512, 16, K)); fam.append((a, b))
+    a = r.standard_normal((512, 16, K)) * 2.0 ** r.integers(-12, 13, size=(512, 16, K))
+    b = r.standard_normal((512, 16, K)) * 2.0 ** r.integers(-12, 13, size=(512, 16, K)); fam.append((a, b))
+    for q in range(16, 34):                                # one term 2^q, the others a hair below each power of two near its last place
+        for small in (1.0, 1.9921875, 3.984375, 7.96875, 15.9375):
+            a = np.full((1, 16, K), small); b = np.ones((1, 16, K))
+            pos = int(r.integers(0, K))
+            a[:, :, pos] = 2.0 ** (q // 2); b[:, :, pos] = 2.0 ** (q - q // 2)
+            fam.append((a, b))
+            a2, b2 = a.copy(), b.copy()                    # and with a cancelling partner
+            a2[:, :, (pos + 5) % K] = -2.0 ** (q // 2); b2[:, :, (pos + 5) % K] = 2.0 ** (q - q // 2)
+            fam.append((a2, b2))
+    worst = 0.0
+    for a, b in fam:
+        a, b = W.to_bf16_grid(a.astype(np.float32)), W.to_bf16_grid(b.astype(np.float32))
+        d = torch.empty((a.shape[0], 16, 16), dtype=torch.float32, device=H.DEV)
+        H.P.moe_diag_mfma_run_sum(H.dev(a, "bf16"), H.dev(b, "bf16"), d)
+        torch.cuda.synchronize()
+        a64, b64 = a.astype(np.float64), b.astype(np.float64)
+        exact = np.einsum("tik,tjk->tij", a64, b64)
+        mass = np.einsum("tik,tjk->tij", np.abs(a64), np.abs(b64))
+        worst = max(worst, float(np.max(np.abs(H.host(d).astype(np.float64) - exact) / mass)))
+    print("worst |error| / sum|x w| for a chain of %d: %.3e = %.3f * 2^-18" % (run, worst, worst * 2.0 ** 18))
+    assert worst <= run * 1.05 * 2.0 ** -18
+
+
 COMBINE_CASES = [W.get_config("c1_tiny_fp32"), small("c2_mixtral", T=333, H=520), small("c3_switch", T=1000, H=64),
                  small("c5_finegrained", T=257, H=264)]
 
