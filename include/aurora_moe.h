@@ -296,8 +296,8 @@ typedef struct {
     double makespan_rounds;  /* sum of round durations (== bmax up to rounding) */
     double makespan_order;   /* Algorithm 1: end of the last flow in its plan (flows wait for their slot) */
     double order_time;       /* aurora_simulate of dest_order */
-    double candidate_time[3];/* aurora_simulate of the three candidate orders (see below) */
-    int32_t order_source;    /* which candidate dest_order grew from: 0, 1 or 2 */
+    double candidate_time[4];/* aurora_simulate of the four candidate orders (see below) */
+    int32_t order_source;    /* which candidate dest_order grew from: 0..3 */
 } aurora_schedule;
 
 /* Transmission order of one all-to-all (Sec. 4.2 Theorem 2 and Algorithm 1;
@@ -315,7 +315,9 @@ typedef struct {
  * what aurora_simulate gives: the best of (0) Algorithm 1's order, (1)
  * destinations by their first round in the Appendix A schedule, (2) an order
  * built while playing the transfer forward (an idle GPU starts the flow whose
- * receiver has the fewest incoming flows, then the largest flow); then neighbouring
+ * receiver has the fewest incoming flows, then the largest flow), (3) the shifted
+ * order i -> i+1, i+2, ... (mod n), contention-free when all flows are equal;
+ * then neighbouring
  * flows of a GPU are exchanged while that shortens the simulated time (at most
  * 64 n trials).  order_time >= port_bound always, >= bmax for equal rates. */
 int aurora_order(int32_t n, const int64_t* D, const double* B, aurora_schedule* out);

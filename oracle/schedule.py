@@ -25,7 +25,7 @@ seeded matrices (tests/golden/order_ratios.txt).  What no pin can decide is
 whether the authors' own implementation breaks ties the same way: the paper
 does not say.
 
-`send_order` is what the library hands to the send buffer: the best of three
+`send_order` is what the library hands to the send buffer: the best of four
 whole-flow orders under `simulate`, improved by adjacent exchanges.
 """
 from __future__ import annotations
@@ -352,6 +352,12 @@ def list_order(D, B=None):
     return full, t
 
 
+def shift_order(n):
+    """GPU i sends to i + 1, i + 2, ... (mod n): in step s the receivers (i + s) mod n are all different, the
+    contention-free order of an all-to-all whose flows are all equal."""
+    return [[(i + s) % n for s in range(1, n)] + [i] for i in range(n)]
+
+
 IMPROVE_MARGIN = Fraction(1, 10 ** 9)     # an exchange must gain more than this fraction of the time
 
 
@@ -388,14 +394,14 @@ def improve_order(D, B, order, max_evals=None):
 
 def send_order(D, B=None, max_evals=None):
     """The whole-flow order handed to the send buffer: the candidate with the smallest
-    `simulate` among Algorithm 1's order, the order read off the rounds and the
-    list order (the earlier candidate wins unless a later one is better by more
-    than IMPROVE_MARGIN), then `improve_order`.  Returns dict(dest_order, time,
-    source (0, 1, 2), candidate_times)."""
-    cands = [alg1_order(D, B)["dest_order"], rounds_order(D, B), list_order(D, B)[0]]
+    `simulate` among Algorithm 1's order, the order read off the rounds, the
+    list order and the shifted order (the earlier candidate wins unless a later
+    one is better by more than IMPROVE_MARGIN), then `improve_order`.  Returns
+    dict(dest_order, time, source (0..3), candidate_times)."""
+    cands = [alg1_order(D, B)["dest_order"], rounds_order(D, B), list_order(D, B)[0], shift_order(len(D))]
     times = [simulate(D, B, c) for c in cands]
     k = 0
-    for c in (1, 2):
+    for c in (1, 2, 3):
         if times[c] < times[k] * (1 - IMPROVE_MARGIN):
             k = c
     order, t = improve_order(D, B, cands[k], max_evals)

@@ -22,7 +22,7 @@ class aurora_schedule(C.Structure):
                 ("alg1_order", C.POINTER(C.c_int32)),
                 ("start", C.POINTER(C.c_double)), ("bmax", C.c_double), ("port_bound", C.c_double),
                 ("makespan_rounds", C.c_double), ("makespan_order", C.c_double), ("order_time", C.c_double),
-                ("candidate_time", C.c_double * 3), ("order_source", C.c_int32)]
+                ("candidate_time", C.c_double * 4), ("order_source", C.c_int32)]
 
 
 class aurora_coloc_times(C.Structure):

@@ -300,7 +300,7 @@ def aurora_order(D, B=None):
             "start": np.array([s.start[i] for i in range(n * n)], dtype=np.float64).reshape(n, n),
             "bmax": s.bmax, "port_bound": s.port_bound, "makespan_rounds": s.makespan_rounds,
             "makespan_order": s.makespan_order, "order_time": s.order_time,
-            "candidate_time": [s.candidate_time[c] for c in range(3)], "order_source": s.order_source,
+            "candidate_time": [s.candidate_time[c] for c in range(4)], "order_source": s.order_source,
         }
     finally:
         lib.aurora_schedule_free(C.byref(s))

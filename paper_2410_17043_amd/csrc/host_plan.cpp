@@ -462,16 +462,20 @@ extern "C" int aurora_order(int32_t n, const int64_t* D, const double* B, aurora
         }
         out->port_bound = pb;
         const std::vector<Round> rounds = plan_rounds(P, out->bmax);
-        std::vector<int32_t> order, by_rounds, by_list;
+        std::vector<int32_t> order, by_rounds, by_list, by_shift((size_t)n * n);
         std::vector<double> start;
         plan_order(P, order, start, &out->makespan_order);
-        // the order for the send buffer: the best of three whole-flow orders when run back to back (an earlier
+        // the order for the send buffer: the best of four whole-flow orders when run back to back (an earlier
         // candidate stays unless a later one is better by more than the margin), then adjacent exchanges
         order_from_rounds(n, rounds, by_rounds);
         order_by_list(n, D, B, by_list);
-        const std::vector<int32_t>* cand[3] = {&order, &by_rounds, &by_list};
+        for (int i = 0; i < n; ++i) {                            // shifted order: in step s GPU i sends to (i + s) mod n
+            for (int sft = 1; sft < n; ++sft) by_shift[(size_t)i * n + sft - 1] = (i + sft) % n;
+            by_shift[(size_t)i * n + n - 1] = i;
+        }
+        const std::vector<int32_t>* cand[4] = {&order, &by_rounds, &by_list, &by_shift};
         int pick = 0;
-        for (int c = 0; c < 3; ++c) {
+        for (int c = 0; c < 4; ++c) {
             out->candidate_time[c] = simulate_order(n, D, B, cand[c]->data());
             if (c > 0 && out->candidate_time[c] < out->candidate_time[pick] * (1.0 - kImproveMargin)) pick = c;
         }

@@ -248,7 +248,7 @@ def test_list_order_replays_under_simulate_and_send_order_is_the_best_candidate(
             # two event loops written separately (one chooses flows while it runs, the other replays a given
             # order) must agree on the completion time
             assert S.simulate(D, B, order) == t
-            cands = [S.alg1_order(D, B)["dest_order"], S.rounds_order(D, B), order]
+            cands = [S.alg1_order(D, B)["dest_order"], S.rounds_order(D, B), order, S.shift_order(n)]
             so = S.send_order(D, B)
             assert so["candidate_times"] == [S.simulate(D, B, c) for c in cands]
             assert so["time"] == S.simulate(D, B, so["dest_order"]) <= min(so["candidate_times"])
