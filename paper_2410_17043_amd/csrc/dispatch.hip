@@ -270,62 +270,99 @@ __global__ __launch_bounds__(1024) void small_rank_kernel(const int32_t* __restr
     traffic_outputs(raw, kept, E, G, capacity, map, expert_count, dest_count, n_dropped);
 }
 
-// Writes the token row at `src` (its first 8 KB already requested into v) to the send rows of the
-// token's k slots; lane j < k holds the row of slot j in my_row (-1: dropped).
-constexpr int kRowLoads = 8;          // 16-byte loads in flight per lane: a whole 8 KB row per wave
-template <int K>
-__device__ __forceinline__ void copy_token_rows(const u32x4* __restrict__ src, u32x4 (&v)[kRowLoads], int my_row, int k, int row16,
-                                                u32x4* __restrict__ send_buf, int lane) {
-    constexpr int KM = (K > 0) ? K : MOE_MAX_K;
-    int rows[KM];
-#pragma unroll
-    for (int j = 0; j < KM; ++j) rows[j] = (j < k) ? __shfl(my_row, j, 64) : -1;
-    for (int c0 = 0; c0 < row16; c0 += 64 * kRowLoads) {
-        if (c0 > 0) {
-#pragma unroll
-            for (int u = 0; u < kRowLoads; ++u) {
-                const int c = c0 + u * 64 + lane;
-                if (c < row16) v[u] = src[c];
-            }
+// Row copying shared by the two scatter kernels.  A wave owns kRowLoads 16-byte loads per lane (8 KB) of input:
+// one piece of one long row (rows beyond 8 KB are cut into pieces, grid.y), one whole row, or `tpw` short rows
+// (a row of 64 << lsh units with tpw << lsh <= kRowLoads), so that the work that does not depend on the row
+// length (segment starts, index loads) is spread over more copying.  The loads and the stores are straight-line
+// code (no loop, no divergent branch around a load): every load of the wave is in flight before the first store,
+// and the stores follow each other without waiting.  row16 = 16-byte units per row.
+constexpr int kRowLoads = 8;
+struct RowGeom {
+    int row16;     // 16-byte units per row
+    int tpw;       // tokens per wave
+    int lsh;       // tpw > 1: a row is 64 << lsh units
+    int pieces;    // tpw == 1: 8 KB pieces per row (grid.y)
+};
+RowGeom row_geometry(int row16, int k) {
+    RowGeom g{row16, 1, 0, (row16 + 64 * kRowLoads - 1) / (64 * kRowLoads)};
+    // Rows of 1, 2 or 4 KB: up to 8, 4 or 2 tokens per wave, as long as a wave writes at most 16 KB (with more
+    // stores behind one wave's loads the fine-grained workload, 4 KB rows to 6 slots, lost a sixth of its rate).
+    for (int l = 0; l < 3; ++l)
+        if (row16 == (64 << l)) {
+            g.lsh = l;
+            for (g.tpw = kRowLoads >> l; g.tpw > 1 && g.tpw * k * (1 << l) > 16; g.tpw >>= 1) {}
         }
+    return g;
+}
+// token (relative to the wave's first) and first unit inside the row of the wave's load u: wave-uniform values
+__device__ __forceinline__ void load_place(const RowGeom& g, int u, int* q, int* c0) {
+    if (g.tpw > 1) {
+        *q = u >> g.lsh;
+        *c0 = (u & ((1 << g.lsh) - 1)) << 6;
+    } else {
+        *q = 0;
+        *c0 = ((int)blockIdx.y * kRowLoads + u) * 64;
+    }
+}
+// Every load is issued whatever the shape: one that has no token or no part of the row left (the tail of T, a row
+// that is not a whole number of 1 KB wave-loads, fewer rows than the wave could take) reads the nearest valid
+// unit again, which costs a cache hit and keeps the code free of branches (and of the copies of all 32 row
+// registers that the compiler makes at every conditional load).
+__device__ __forceinline__ void load_rows(const u32x4* __restrict__ x, const RowGeom& g, int t0, int T, int lane,
+                                          u32x4 (&v)[kRowLoads]) {
+#pragma unroll
+    for (int u = 0; u < kRowLoads; ++u) {
+        int q, c0;
+        load_place(g, u, &q, &c0);
+        const int t = min(t0 + min(q, g.tpw - 1), T - 1);
+        v[u] = x[(size_t)t * g.row16 + min(c0 + lane, g.row16 - 1)];
+    }
+}
+// lane q * k + j holds the send row of slot j of the wave's token q in my_row (-1: dropped, or no such token)
+template <int K>
+__device__ __forceinline__ void store_rows(const u32x4 (&v)[kRowLoads], const RowGeom& g, int my_row, int k, int lane,
+                                           u32x4* __restrict__ send_buf) {
+    constexpr int KM = (K > 0) ? K : MOE_MAX_K;
+#pragma unroll
+    for (int u = 0; u < kRowLoads; ++u) {
+        int q, c0;
+        load_place(g, u, &q, &c0);
+        if (q >= g.tpw || c0 >= g.row16) continue;                // wave-uniform
 #pragma unroll
         for (int j = 0; j < KM; ++j) {
-            if (rows[j] >= 0) {
-                u32x4* dst = send_buf + (size_t)rows[j] * row16;
-#pragma unroll
-                for (int u = 0; u < kRowLoads; ++u) {
-                    const int c = c0 + u * 64 + lane;
-                    if (c < row16) __builtin_nontemporal_store(v[u], dst + c);
-                }
-            }
+            if (j >= k) continue;
+            const int row = __builtin_amdgcn_readlane(my_row, q * k + j);
+            if (row >= 0 && c0 + lane < g.row16) __builtin_nontemporal_store(v[u], send_buf + (size_t)row * g.row16 + c0 + lane);
         }
     }
 }
 
-// One wave per token.  row16 = 16-byte units per row.
 template <int K>
 __global__ __launch_bounds__(256) void scatter_kernel(const u32x4* __restrict__ x, const int32_t* __restrict__ idx,
                                                       const int32_t* __restrict__ slot_rank,
                                                       const int32_t* __restrict__ raw_count, int T, int k_rt, int E,
-                                                      int capacity, SegMap map, int row16, u32x4* __restrict__ send_buf,
-                                                      int32_t* __restrict__ slot_to_row, int32_t* __restrict__ row_to_slot,
-                                                      int32_t* __restrict__ seg_offset, int32_t* __restrict__ seg_expert) {
+                                                      int capacity, SegMap map, RowGeom g,
+                                                      u32x4* __restrict__ send_buf, int32_t* __restrict__ slot_to_row,
+                                                      int32_t* __restrict__ row_to_slot, int32_t* __restrict__ seg_offset,
+                                                      int32_t* __restrict__ seg_expert) {
     __shared__ int seg_first[MOE_MAX_E];   // E > 64: first send row of each expert
     __shared__ int cnt_of[MOE_MAX_E];      // E > 64: total of each expert
     __shared__ int wave_first[4][64];      // E <= 64: first send row of each expert, one copy per wave
     __shared__ int wave_sum[4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int t = blockIdx.x * 4 + wave;
+    const int t0 = __builtin_amdgcn_readfirstlane((blockIdx.x * 4 + wave) * g.tpw);   // first token of this wave
     const int k = (K > 0) ? K : k_rt;
-    const bool live = t < T;
-    const u32x4* src = x + (size_t)(live ? t : 0) * row16;
+    const int n_slots = T * k;
+    const int s_mine = t0 * k + lane;                         // lane q * k + j looks after slot j of token t0 + q
+    const bool has_slot = lane < g.tpw * k && s_mine < n_slots;
+    const bool first_piece = blockIdx.y == 0;                 // the pieces of a long row work out the same send rows
     // Memory returns a wave's loads in the order they were issued, so the small loads that the send rows
-    // depend on go out first (all independent of each other: one round trip), then the 8 KB of the token row;
-    // the rows are worked out while the row data is still in flight.
+    // depend on go out first (all independent of each other: one round trip), then the 8 KB of token rows;
+    // the send rows are worked out while the row data is still in flight.
     int slot_e = -1, slot_rank_v = -1;
-    if (live && lane < k) {
-        slot_e = idx[t * k + lane];
-        slot_rank_v = slot_rank[t * k + lane];
+    if (has_slot) {
+        slot_e = idx[s_mine];
+        slot_rank_v = slot_rank[s_mine];
     }
     const int p_blk = (E <= 64) ? lane : threadIdx.x;       // send-order position this thread looks after
     const int ex = (p_blk < E) ? map.seg_expert[p_blk] : 0;
@@ -334,11 +371,7 @@ __global__ __launch_bounds__(256) void scatter_kernel(const u32x4* __restrict__ 
     // plain (cacheable) loads: the gate has just read x, so the rows come from the memory-side cache; the
     // send rows are written with streaming stores
     u32x4 v[kRowLoads];
-#pragma unroll
-    for (int u = 0; u < kRowLoads; ++u) {
-        const int c = u * 64 + lane;
-        if (live && c < row16) v[u] = src[c];
-    }
+    load_rows(x, g, t0, T, lane, v);
     __builtin_amdgcn_sched_barrier(0);
     // Segment starts in send order.  Up to 64 experts every wave does the prefix sum for itself (lane p =
     // position p, no block barrier); beyond, the block shares one through LDS.
@@ -354,7 +387,7 @@ __global__ __launch_bounds__(256) void scatter_kernel(const u32x4* __restrict__ 
         }
         const int excl = incl - cnt;
         if (lane < E) wave_first[wave][ex] = excl;
-        if (blockIdx.x == 0 && wave == 0 && lane < E) {
+        if (blockIdx.x == 0 && first_piece && wave == 0 && lane < E) {
             seg_offset[lane] = excl;
             seg_expert[lane] = ex;
             if (lane == E - 1) seg_offset[E] = incl;
@@ -382,7 +415,7 @@ __global__ __launch_bounds__(256) void scatter_kernel(const u32x4* __restrict__ 
         const int excl = before + incl - cnt;
         if (p_blk < E) {
             seg_first[ex] = excl;
-            if (blockIdx.x == 0) {
+            if (blockIdx.x == 0 && first_piece) {
                 seg_offset[p_blk] = excl;
                 seg_expert[p_blk] = ex;
                 if (p_blk == E - 1) seg_offset[E] = excl + cnt;
@@ -390,19 +423,18 @@ __global__ __launch_bounds__(256) void scatter_kernel(const u32x4* __restrict__ 
         }
         __syncthreads();
     }
-    if (!live) return;
-    // send rows of this token's slots: lane j < k works out slot j, then all lanes learn the k rows
+    if (t0 >= T) return;
+    // send rows of this wave's slots, one per lane
     int my_row = -1;
-    if (lane < k) {
-        const int s = t * k + lane;
+    if (has_slot) {
         const int e = slot_e, rank = slot_rank_v;
         if (e >= 0 && e < E && rank >= 0 && (capacity <= 0 || rank < capacity)) {
             my_row = ((E <= 64) ? wave_first[wave][e] : seg_first[e]) + rank;
-            row_to_slot[my_row] = s;
+            if (first_piece) row_to_slot[my_row] = s_mine;
         }
-        slot_to_row[s] = my_row;
+        if (first_piece) slot_to_row[s_mine] = my_row;
     }
-    copy_token_rows<K>(src, v, my_row, k, row16, send_buf, lane);
+    store_rows<K>(v, g, my_row, k, lane, send_buf);
 }
 
 // ------------------------------------------------------------------------------ chunked layout
@@ -539,28 +571,31 @@ __global__ __launch_bounds__(kLayoutThreads) void chunk_layout_kernel(ChunkTable
     }
 }
 
-// One wave per token, like scatter_kernel; the send row of a kept slot comes from the chunk tables.
+// Waves take tokens as in scatter_kernel; the send row of a kept slot comes from the chunk tables.
 template <int K>
 __global__ __launch_bounds__(256) void scatter_chunks_kernel(const u32x4* __restrict__ x, const int32_t* __restrict__ idx,
                                                              const int32_t* __restrict__ slot_rank, int T, int k_rt, int E,
-                                                             int capacity, SegMap map, ChunkTables tb, int row16,
+                                                             int capacity, SegMap map, ChunkTables tb, RowGeom g,
                                                              u32x4* __restrict__ send_buf, int32_t* __restrict__ slot_to_row,
                                                              int32_t* __restrict__ row_to_slot) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int t = blockIdx.x * 4 + wave;
+    const int t0 = __builtin_amdgcn_readfirstlane((blockIdx.x * 4 + wave) * g.tpw);
     const int k = (K > 0) ? K : k_rt;
-    if (t >= T) return;
-    const u32x4* src = x + (size_t)t * row16;
-    u32x4 v[kRowLoads];
-#pragma unroll
-    for (int u = 0; u < kRowLoads; ++u) {
-        const int c = u * 64 + lane;
-        if (c < row16) v[u] = src[c];
+    if (t0 >= T) return;
+    const int s_mine = t0 * k + lane;
+    const bool has_slot = lane < g.tpw * k && s_mine < T * k;
+    const bool first_piece = blockIdx.y == 0;
+    int e = -1, rank = -1;
+    if (has_slot) {
+        e = idx[s_mine];
+        rank = slot_rank[s_mine];
     }
+    __builtin_amdgcn_sched_barrier(0);
+    u32x4 v[kRowLoads];
+    load_rows(x, g, t0, T, lane, v);
+    __builtin_amdgcn_sched_barrier(0);
     int my_row = -1;
-    if (lane < k) {
-        const int s = t * k + lane;
-        const int e = idx[s], rank = slot_rank[s];
+    if (has_slot) {
         if (e >= 0 && e < E && rank >= 0 && (capacity <= 0 || rank < capacity)) {
             const int d = map.expert_gpu[e];
             const int q = tb.expert_first[e] + rank;          // position in the destination's sequence
@@ -571,11 +606,11 @@ __global__ __launch_bounds__(256) void scatter_chunks_kernel(const u32x4* __rest
             }
             const int c = tb.p_chunk[lo];
             my_row = tb.c_row0[c] + q - tb.c_cumlo[c];
-            row_to_slot[my_row] = s;
+            if (first_piece) row_to_slot[my_row] = s_mine;
         }
-        slot_to_row[s] = my_row;
+        if (first_piece) slot_to_row[s_mine] = my_row;
     }
-    copy_token_rows<K>(src, v, my_row, k, row16, send_buf, lane);
+    store_rows<K>(v, g, my_row, k, lane, send_buf);
 }
 
 int build_segmap(const moe_shape& s, const int32_t* expert_to_gpu, const int32_t* dest_order, SegMap* m) {
@@ -641,12 +676,13 @@ int launch_scatter(const moe_shape& s, const RankScratch& sc, const SegMap& map,
                    void* send_buf, int32_t* slot_to_row, int32_t* row_to_slot, int32_t* seg_offset, int32_t* seg_expert,
                    hipStream_t st) {
     const int row16 = (int)((int64_t)s.H * elem_size(s.dtype) / 16);
-    const dim3 grid((s.T + 3) / 4);
+    const RowGeom g = row_geometry(row16, s.k);
+    const dim3 grid((s.T + 4 * g.tpw - 1) / (4 * g.tpw), g.pieces);
     const u32x4* xs = reinterpret_cast<const u32x4*>(x);
     u32x4* sb = reinterpret_cast<u32x4*>(send_buf);
 #define MOE_SCATTER(KK)                                                                                          \
     hipLaunchKernelGGL(scatter_kernel<KK>, grid, dim3(256), 0, st, xs, topk_idx, sc.slot_rank, sc.raw_count, s.T, \
-                       s.k, s.E, s.capacity, map, row16, sb, slot_to_row, row_to_slot, seg_offset, seg_expert)
+                       s.k, s.E, s.capacity, map, g, sb, slot_to_row, row_to_slot, seg_offset, seg_expert)
     if (s.k == 1) MOE_SCATTER(1);
     else if (s.k == 2) MOE_SCATTER(2);
     else MOE_SCATTER(0);
@@ -857,12 +893,13 @@ extern "C" int moe_dispatch_chunks(moe_ctx* ctx, const moe_chunk_plan* plan, con
                        s.capacity, plan->map, chunk_offset, piece_offset, piece_expert, n_pieces);
     MOE_LAUNCH_CHECK("chunk_layout_kernel");
     const int row16 = (int)((int64_t)s.H * elem_size(s.dtype) / 16);
-    const dim3 grid((s.T + 3) / 4);
+    const RowGeom g = row_geometry(row16, s.k);
+    const dim3 grid((s.T + 4 * g.tpw - 1) / (4 * g.tpw), g.pieces);
     const u32x4* xs = reinterpret_cast<const u32x4*>(x);
     u32x4* sb = reinterpret_cast<u32x4*>(send_buf);
 #define MOE_SCATTER(KK)                                                                                              \
     hipLaunchKernelGGL(scatter_chunks_kernel<KK>, grid, dim3(256), 0, st, xs, topk_idx, ctx->slot_rank, s.T, s.k, s.E, \
-                       s.capacity, plan->map, plan->tb, row16, sb, slot_to_row, row_to_slot)
+                       s.capacity, plan->map, plan->tb, g, sb, slot_to_row, row_to_slot)
     if (s.k == 1) MOE_SCATTER(1);
     else if (s.k == 2) MOE_SCATTER(2);
     else MOE_SCATTER(0);

@@ -1127,9 +1127,10 @@ static int ffn_impl(const void* recv, int32_t R, const int32_t* seg_offset, cons
     if (ev) MOE_HIP(hipEventRecord(ev[0], st));
     // gathered tiles address their rows by 32-bit byte offsets from the tile's first row
     const int gather = (dtype == MOE_BF16 && (size_t)R * (size_t)std::max(H, F) * 2 <= 0xFFFFFFFFull) ? 1 : 0;
-    // a thread per segment, in whole waves: with a handful of segments one wave does everything and the
-    // block-wide barriers of the map cost nothing
-    const int map_threads = std::min(kMapThreads, std::max(64, (nseg + 63) / 64 * 64));
+    // A thread per segment, and whole waves write the row-offset tables of the gathered tiles.  With a handful of
+    // segments a quarter of the block does it as fast and its barriers are cheaper (10 against 12.7 us with 8
+    // segments); one wave alone was too few for the tables (18 against 12 us with 64 segments, 10 k table rows).
+    const int map_threads = (nseg <= 16) ? 256 : kMapThreads;
     hipLaunchKernelGGL(tilemap_kernel, dim3(1), dim3(map_threads), 0, st, seg_offset, seg_expert, nseg, R, bm, n_local, gather,
                        (R + bm - 1) / bm + nseg, m);
     MOE_LAUNCH_CHECK("tilemap_kernel");
