@@ -58,14 +58,15 @@ __global__ __launch_bounds__(256, 1) void mfma_only_kernel(int iters, float* __r
 
 // dst0[i] = dst1[i] = src[i]: a wave per 8 KB piece, 16 bytes per lane and access, the whole piece requested
 // before the first store, cacheable loads and streaming stores (the fastest of the plain variants tried:
-// streaming loads, fewer loads in flight and several pieces per wave were all slower).
+// streaming loads, fewer loads in flight and several pieces per wave were all slower).  Every load is issued
+// unconditionally (past the end a lane reads the last unit again): a load under a condition makes the compiler
+// copy all 32 data registers and wait for each load before it issues the next.
 __global__ __launch_bounds__(256) void copy_1r2w_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst0,
                                                         u32x4* __restrict__ dst1, size_t n16) {
     const size_t base = ((size_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 512 + (threadIdx.x & 63);
     u32x4 v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u)
-        if (base + u * 64 < n16) v[u] = src[base + u * 64];
+    for (int u = 0; u < 8; ++u) v[u] = src[min(base + u * 64, n16 - 1)];
 #pragma unroll
     for (int u = 0; u < 8; ++u)
         if (base + u * 64 < n16) __builtin_nontemporal_store(v[u], dst0 + base + u * 64);
