@@ -41,22 +41,21 @@ template <> struct Pack<MOE_F32> {
 template <int DT, int K, bool STREAM>
 __global__ __launch_bounds__(256) void combine_kernel(const u32x4* __restrict__ ret, const int32_t* __restrict__ slot_to_row,
                                                       const float* __restrict__ topk_w, const u32x4* __restrict__ shared_out,
-                                                      int T, int k_rt, int row16, u32x4* __restrict__ y) {
+                                                      int T, int row16, u32x4* __restrict__ y) {
     constexpr int V = Pack<DT>::V;
-    constexpr int KM = (K > 0) ? K : MOE_MAX_K;
+    constexpr int KM = K;
     const int lane = threadIdx.x & 63;
     const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= T) return;
-    const int k = (K > 0) ? K : k_rt;
     int rows[KM];
     float w[KM];
 #pragma unroll
     for (int j = 0; j < KM; ++j) {
-        rows[j] = (j < k) ? slot_to_row[(size_t)t * k + j] : -1;
-        w[j] = (j < k) ? topk_w[(size_t)t * k + j] : 0.f;
+        rows[j] = slot_to_row[(size_t)t * K + j];
+        w[j] = topk_w[(size_t)t * K + j];
     }
     // CPT 16-byte chunks per lane per trip, about eight independent row loads in flight before the first use
-    constexpr int CPT = (K > 0 && K < 4) ? 8 / K : 2;
+    constexpr int CPT = (K < 4) ? 8 / K : 2;
     for (int c0 = lane; c0 < row16; c0 += 64 * CPT) {
         u32x4 q[CPT][KM];
 #pragma unroll
@@ -96,6 +95,54 @@ __global__ __launch_bounds__(256) void combine_kernel(const u32x4* __restrict__ 
     }
 }
 
+// Any k: one token and 1 KB of its rows per wave, four source rows in flight at a time.  The loads are issued
+// unconditionally (a slot past k or a dropped one reads a valid row whose value is not used): with the loads of
+// a 16-slot array under conditions the compiler kept the whole array in registers (217 of them) and waited
+// for each load in turn.
+template <int DT, bool STREAM>
+__global__ __launch_bounds__(256) void combine_any_k_kernel(const u32x4* __restrict__ ret, const int32_t* __restrict__ slot_to_row,
+                                                            const float* __restrict__ topk_w, const u32x4* __restrict__ shared_out,
+                                                            int T, int k, int row16, u32x4* __restrict__ y) {
+    constexpr int V = Pack<DT>::V;
+    const int lane = threadIdx.x & 63;
+    const int t = __builtin_amdgcn_readfirstlane(blockIdx.x * 4 + (threadIdx.x >> 6));
+    if (t >= T) return;
+    const int c0 = blockIdx.y * 64;
+    const int c = min(c0 + lane, row16 - 1);
+    float acc[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) acc[v] = 0.f;
+    for (int j0 = 0; j0 < k; j0 += 4) {
+        int rows[4];
+        float w[4];
+        u32x4 d[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int j = min(j0 + i, k - 1);
+            rows[i] = (j0 + i < k) ? slot_to_row[(size_t)t * k + j] : -1;
+            w[i] = topk_w[(size_t)t * k + j];
+            const u32x4* p = ret + (size_t)max(rows[i], 0) * row16 + c;
+            d[i] = STREAM ? __builtin_nontemporal_load(p) : *p;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            if (rows[i] >= 0) {
+                float f[V];
+                Pack<DT>::unpack(d[i], f);
+#pragma unroll
+                for (int v = 0; v < V; ++v) acc[v] = fmaf(w[i], f[v], acc[v]);
+            }
+        }
+    }
+    if (shared_out) {
+        float f[V];
+        Pack<DT>::unpack(shared_out[(size_t)t * row16 + c], f);
+#pragma unroll
+        for (int v = 0; v < V; ++v) acc[v] += f[v];
+    }
+    if (c0 + lane < row16) __builtin_nontemporal_store(Pack<DT>::pack(acc), y + (size_t)t * row16 + c0 + lane);
+}
+
 // Rows that were just written by the return transfer are still in the memory-side cache (256 MB) when they
 // are not too many: plain loads then (17 against 19 us at the Mixtral-shape share, 67 MB); beyond half of that
 // cache plain loads only evict each other (103 against 86 us at 403 MB) and streaming loads are used.
@@ -110,10 +157,13 @@ int launch_combine(const moe_ctx* c, const void* ret, const int32_t* s2r, const 
     const u32x4* r = reinterpret_cast<const u32x4*>(ret);
     const u32x4* sh = reinterpret_cast<const u32x4*>(shared);
     u32x4* yo = reinterpret_cast<u32x4*>(y);
-    if (s.k == 1) hipLaunchKernelGGL((combine_kernel<DT, 1, STREAM>), grid, dim3(256), 0, st, r, s2r, w, sh, s.T, s.k, row16, yo);
-    else if (s.k == 2) hipLaunchKernelGGL((combine_kernel<DT, 2, STREAM>), grid, dim3(256), 0, st, r, s2r, w, sh, s.T, s.k, row16, yo);
-    else if (s.k == 6) hipLaunchKernelGGL((combine_kernel<DT, 6, STREAM>), grid, dim3(256), 0, st, r, s2r, w, sh, s.T, s.k, row16, yo);
-    else hipLaunchKernelGGL((combine_kernel<DT, 0, STREAM>), grid, dim3(256), 0, st, r, s2r, w, sh, s.T, s.k, row16, yo);
+    if (s.k == 1) hipLaunchKernelGGL((combine_kernel<DT, 1, STREAM>), grid, dim3(256), 0, st, r, s2r, w, sh, s.T, row16, yo);
+    else if (s.k == 2) hipLaunchKernelGGL((combine_kernel<DT, 2, STREAM>), grid, dim3(256), 0, st, r, s2r, w, sh, s.T, row16, yo);
+    else if (s.k == 6) hipLaunchKernelGGL((combine_kernel<DT, 6, STREAM>), grid, dim3(256), 0, st, r, s2r, w, sh, s.T, row16, yo);
+    else {
+        const dim3 grid_any((s.T + 3) / 4, (row16 + 63) / 64);
+        hipLaunchKernelGGL((combine_any_k_kernel<DT, STREAM>), grid_any, dim3(256), 0, st, r, s2r, w, sh, s.T, s.k, row16, yo);
+    }
     MOE_LAUNCH_CHECK("combine_kernel");
     return MOE_OK;
 }
