@@ -123,6 +123,14 @@ DISPATCH_CASES = [
     (small("c3_switch", T=20011, H=32), None),
     (small("c2_mixtral", T=8193, H=64), 0),               # 16386 slots, just over the single-block limit
     (small("c2_mixtral", T=8192, H=64), 0),               # 16384 slots, the single-block limit itself
+    # row lengths that pick the other copy geometries: several short rows per wave (1, 2, 4 KB rows; a ragged
+    # last wave), rows longer than a wave's 8 KB cut into pieces (a whole number of pieces and a ragged one)
+    (small("c2_mixtral", T=203, H=512), 0),               # 1 KB rows: 8 tokens per wave
+    (small("c3_switch", T=517, H=1024), 9),               # 2 KB rows, k = 1: 4 tokens per wave, dropped slots
+    (small("c5_finegrained", T=131, H=512), 0),           # 1 KB rows to 6 slots: 2 tokens per wave
+    (small("c4b_coloc", T=99, H=2048), 0),                # 4 KB rows: 2 tokens per wave
+    (small("c2_mixtral", T=77, H=8192), 0),               # 16 KB rows: two pieces
+    (small("c1_tiny_fp32", T=50, H=2304, E=5, k=3, G=5), 0),   # 9 KB rows: a full piece and a 1 KB one
 ]
 
 
@@ -231,7 +239,9 @@ def test_dispatch_alone_and_after_in_place_index_rewrite(H, cfg):
 
 CHUNK_CASES = [small("c2_mixtral", T=300, H=264), small("c3_switch", T=700, H=128), small("c5_finegrained", T=260, H=64),
                small("c3_switch", T=40, H=64),                 # most experts get no token at all
-               small("c1_tiny_fp32", T=37, H=100, E=5, k=3, G=5), small("c5_finegrained", T=3000, H=64, E=160, k=9, G=16)]
+               small("c1_tiny_fp32", T=37, H=100, E=5, k=3, G=5), small("c5_finegrained", T=3000, H=64, E=160, k=9, G=16),
+               small("c2_mixtral", T=203, H=512), small("c3_switch", T=517, H=1024),      # several short rows per wave
+               small("c2_mixtral", T=77, H=8192)]                                          # long rows in pieces
 
 
 @pytest.mark.parametrize("cfg", CHUNK_CASES, ids=lambda c: "%s-T%d-E%d-k%d-G%d" % (c.name, c.T, c.E, c.k, c.G))
@@ -399,10 +409,13 @@ def test_mfma_run_sum_stays_inside_the_error_model_of_the_gate(H, run):
 
 
 COMBINE_CASES = [W.get_config("c1_tiny_fp32"), small("c2_mixtral", T=333, H=520), small("c3_switch", T=1000, H=64),
-                 small("c5_finegrained", T=257, H=264)]
+                 small("c5_finegrained", T=257, H=264),
+                 # k outside 1, 2, 6: the loop kernel (a whole number of groups of four rows, a ragged one, the limit)
+                 small("c2_mixtral", T=211, H=520, E=24, k=4), small("c1_tiny_fp32", T=37, H=100, E=5, k=3, G=5),
+                 small("c5_finegrained", T=65, H=264, E=160, k=9, G=16), small("c3_switch", T=40, H=1024, E=256, k=16, G=64)]
 
 
-@pytest.mark.parametrize("cfg", COMBINE_CASES, ids=lambda c: c.name)
+@pytest.mark.parametrize("cfg", COMBINE_CASES, ids=lambda c: "%s-T%d-H%d-k%d" % (c.name, c.T, c.H, c.k))
 @pytest.mark.parametrize("with_shared", [False, True])
 def test_combine(H, cfg, with_shared):
     inp = W.make_layer_inputs(cfg)
