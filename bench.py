@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM-side bytes per launch of the first FFN GEMM at c2_mixtral from rocprofv3 counters (FETCH_SIZE x 2.0 +
 # WRITE_SIZE x 1.0, see profiles/bench_c2_mixtral_layer_share.md), valid for the kernel source whose SHA-256
 # starts with the digest below; reported as null as soon as ffn.hip differs from what the counters saw.
-GEMM1_TRAFFIC = {"c2_mixtral": {"bytes": 3.9031e6 * 1024 * 2.0 + 6.6752e5 * 1024, "ffn_hip_sha256": "3f2a8813775dec52"}}
+GEMM1_TRAFFIC = {"c2_mixtral": {"bytes": 3.9033e6 * 1024 * 2.0 + 6.6752e5 * 1024, "ffn_hip_sha256": "05b0c7d1763f9afd"}}
 
 
 def gemm1_traffic_bytes(name):
@@ -474,12 +474,32 @@ def measure_stages(torch, wl, cfg, reps):
     }
     if cfg.n_shared:
         rate["shared_ffn_TFLOPs"] = 2.0 * (n_up + 1) * T * H * F * cfg.n_shared / (stage_ms["shared_ffn"] * 1e-3) / 1e12
+    if cfg.dtype == "bf16":
+        rate["decode_share"] = decode_share(torch, wl, cfg, reps)
     achieved = flops_gemm1 / (gemm_ms[1] * 1e-3) / 1e12
     roof = {"kernel": "gemm_bf16_kernel<%s> (first FFN GEMM with the activation)" % {0: "SiLU", 1: "GELU", 2: "SwiGLU"}[cfg.act],
             "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
             "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None, "launch_ms": float(gemm_ms[1]),
             "flops_per_launch": flops_gemm1}
     return stage_ms, rate, roof
+
+
+def decode_share(torch, wl, cfg, reps, rows=32):
+    """The expert FFN over a decode-sized share, for information beside the stages (not part of the step): the
+    first `rows` received rows as one segment of the first local expert.  Every weight of that expert is used
+    once, so the figure of merit is the rate at which the weights stream."""
+    import paper_2410_17043_amd as P
+    dev = wl["recv"].device
+    i32 = dict(dtype=torch.int32, device=dev)
+    rows = min(rows, wl["R"])
+    off, exp = torch.tensor([0, rows], **i32), torch.tensor([0], **i32)
+    out = torch.empty((rows, cfg.H), dtype=wl["recv"].dtype, device=dev)
+    ws = torch.empty(P.moe_ffn_workspace_bytes(rows, cfg.H, cfg.F, cfg.act, cfg.dtype), dtype=torch.uint8, device=dev)
+    table = wl["keep"][5]
+    b = P.bind_expert_ffn(wl["recv"], rows, off, exp, 1, table, cfg.H, cfg.F, cfg.act, cfg.dtype, out, ws)
+    ms = time_graph(torch, capture(torch, lambda: b(torch.cuda.current_stream().cuda_stream), 10), reps, 10)
+    w_bytes = (3 if cfg.act == 2 else 2) * cfg.H * cfg.F * 2
+    return {"rows": rows, "ffn_us": round(ms * 1e3, 1), "weights_GBps": round(w_bytes / (ms * 1e-3) / 1e9, 1)}
 
 
 def config_of(cfg, wl, share):

@@ -21,6 +21,9 @@
 // share an XCD's L2 form a compact patch and all XCDs sweep the N-tiles in step (see
 // tile_of_block); the tiles of a mostly empty last round are cut along K (see plan_tail).
 //
+// Shares of at most 64 rows (bf16) take a pair of weight-streaming kernels instead (gemm_bf16_skinny_kernel):
+// 32- or 64-row tiles, 256-byte bursts per weight row, the LDS ring given to loads in flight.
+//
 // fp32 path (correctness configuration): plain 64x64x16 LDS-tiled vector-ALU GEMM.
 #include "common.h"
 #include <algorithm>
@@ -924,6 +927,235 @@ __global__ __launch_bounds__(256) void gemm_bf16_tail_kernel(TileMap m, int N, i
     flush_rows<EPI>(i, i + 1, lds, row0, nrows, rel, tile_n * EpiGeom<EPI>::NOUT, N, C, ldc);
 }
 
+// ------------------------------------------------------------------------------------------------
+// Shares of at most 64 rows (decode-sized).  The FLOPs are negligible and every weight is used once: the job
+// is to stream the weights at HBM speed.  The big kernel does that at a third of HBM speed, for two reasons
+// that its compute-bound design does not care about: it keeps only 32 KB of weight loads outstanding per CU
+// (the other half of its ring is the mostly empty 256-row A tile), and it reads a weight row 64 bytes at a
+// time, one visit to a DRAM page per 64 bytes.  Here a tile is 64 rows x 128 weight rows and a stage of the
+// LDS ring is 128 elements of K: a wave-load fetches 4 rows x 256 contiguous bytes, a stage is 16 KB of A and
+// 32 KB of weights, three stages fit and two of them (64 KB of weights) are always in flight.  Wave w owns
+// weight rows 32 w .. 32 w + 31 of the tile (SwiGLU: 16 gate rows, then the 16 up rows of the same output
+// columns) and all 64 rows of A: 2 x 1 tiles of v_mfma_f32_32x32x16_bf16, eight k-steps per stage.  A wave
+// loads the weight rows it reads itself; the A tile is shared (one barrier per stage).  With fewer tiles than
+// CUs every tile is cut along K into `parts` pieces (fp32 partial tiles, added in piece order by a second
+// kernel: results do not depend on the run).
+//
+// LDS layout of a stage: blocks of 1 KB = 4 rows x 16 chunks of 16 bytes, filled by ONE wave-wide
+// direct-to-LDS load (lane l fills slot l).  Inside a block slot(r, c) = 16 r + (c ^ (4 r + blk % 4)):
+// the 16 lanes that an MFMA operand read serves at a time (16 consecutive rows = 4 blocks, same chunk) then
+// fall on 16 different values of slot % 16, i.e. on all 64 banks once.
+// MT = 1 or 2 MFMA row tiles: shares of at most 32 rows take 32-row tiles, whose smaller A part leaves room for a
+// fourth stage (96 KB of weights in flight).
+constexpr int SBN = 128;                                 // weight rows per tile
+constexpr int SKW = 128;                                 // elements of K per stage (256 bytes of a row)
+template <int MT> struct SkinnyGeom {
+    static constexpr int BM_ = 32 * MT;                  // rows per tile
+    static constexpr int A_BYTES = BM_ * SKW * 2;        // 8 or 16 KB
+    static constexpr int STAGE = A_BYTES + SBN * SKW * 2;   // 40 or 48 KB
+    static constexpr int STAGES = (MT == 1) ? 4 : 3;
+    static constexpr int LDS = STAGES * STAGE;           // 160 or 144 KB
+    static constexpr int LOADS = 2 * MT + 8;             // wave-loads per stage and wave
+    static constexpr size_t PARTIAL = (size_t)BM_ * SBN * sizeof(float);   // one fp32 partial tile
+};
+constexpr int kSkinnyRows = 64;                          // shares up to this many rows take this path
+
+struct SkinnyPlan {
+    int parts;     // pieces per tile
+    int per;       // stages per piece (the last piece may be shorter)
+};
+__host__ __device__ __forceinline__ SkinnyPlan plan_skinny(int total, int ncu, int ns) {
+    SkinnyPlan p{1, ns};
+    if (total <= 0 || total >= ncu) return p;
+    int parts = min(min(ncu / total, ns / 2), 32);       // at least 2 stages per piece
+    if (parts < 2) return p;
+    p.per = (ns + parts - 1) / parts;
+    p.parts = (ns + p.per - 1) / p.per;
+    return p;
+}
+
+// byte offset of (row, 16-byte chunk c of the stage's 256 bytes) inside a tile region
+__device__ __forceinline__ int skinny_off(int row, int c) {
+    const int blk = row >> 2, r = row & 3;
+    return (blk << 10) + (((r << 4) + (c ^ ((r << 2) | (blk & 3)))) << 4);
+}
+
+// Activation and store of a wave's (32 MT) x 32 block of products held in the MFMA result layout: acc[i][e] is
+// row i * 32 + lane % 32 of the tile and weight row 32 w + (e / 4) * 8 + (lane / 32) * 4 + e % 4.
+template <int EPI, int MT>
+__device__ __forceinline__ void skinny_store(const f32x16 (&acc)[MT], int wave, int lane, int row0, int nrows,
+                                             const int32_t* __restrict__ rel, int n0, int N, uint16_t* __restrict__ C, int ldc) {
+    const int fr = lane & 31, fk = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+        const int gr = i * 32 + fr;
+        if (gr >= nrows) continue;
+        uint16_t* crow = C + (size_t)(row0 + (rel ? rel[gr] : gr)) * ldc;
+#pragma unroll
+        for (int g = 0; g < ((EPI == EPI_SWIGLU) ? 2 : 4); ++g) {
+            float v[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float up = (EPI == EPI_SWIGLU) ? acc[i][4 * (g + 2) + t] : 0.f;
+                v[t] = epilogue_bf16<EPI>(acc[i][4 * g + t], up);
+            }
+            const int col = n0 + ((EPI == EPI_SWIGLU) ? wave * 16 : wave * 32) + g * 8 + fk * 4;
+            if (col < N) *reinterpret_cast<u32x2*>(crow + col) = u32x2{pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+        }
+    }
+}
+
+template <int EPI, int MT>
+__global__ __launch_bounds__(256, 1) void gemm_bf16_skinny_kernel(const uint16_t* __restrict__ A, int lda, TileMap m,
+                                                                  ExpertTable tab, int which0, int which1, int N, int K,
+                                                                  uint16_t* __restrict__ C, int ldc, int tiles_n, int ncu,
+                                                                  float* __restrict__ partial) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    using G = SkinnyGeom<MT>;
+    constexpr int NOUT = (EPI == EPI_SWIGLU) ? SBN / 2 : SBN;
+    const int n_tiles_m = *m.n_tiles;
+    const int total = n_tiles_m * tiles_n;
+    const int ns_all = K / SKW;
+    const SkinnyPlan plan = plan_skinny(total, ncu, ns_all);
+    if ((int)blockIdx.x >= total * plan.parts) return;
+    const int tile_id = blockIdx.x % total, piece = blockIdx.x / total;
+    const int tile_m = tile_id % n_tiles_m, tile_n = tile_id / n_tiles_m;
+    const int row0 = __builtin_amdgcn_readfirstlane(m.row0[tile_m]);
+    const int nrows = __builtin_amdgcn_readfirstlane(m.nrows[tile_m]);
+    const int ex = __builtin_amdgcn_readfirstlane(m.expert[tile_m]);
+    const int32_t* rel = __builtin_amdgcn_readfirstlane(m.gather[tile_m]) ? m.rel + (size_t)tile_m * kRelPitch : nullptr;
+    auto pick = [&](int which) -> const uint16_t* {
+        return reinterpret_cast<const uint16_t*>(which == 0 ? tab.w1[ex] : which == 1 ? tab.w_up[ex] : tab.w_down[ex]);
+    };
+    const uint16_t* B0 = pick(which0);
+    const uint16_t* B1 = (EPI == EPI_SWIGLU) ? pick(which1) : B0;
+    const int n0 = tile_n * NOUT;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int s_lo = piece * plan.per;
+    const int ns = min(plan.per, ns_all - s_lo);
+
+    // What this lane fetches.  A: blocks NA wave .. NA wave + NA - 1 of the 4 NA (NA = 2 MT); weights: blocks
+    // 8 wave .. 8 wave + 7 of the 32 (the rows this wave reads).  In block blk the lane has row lane / 16 and
+    // chunk (lane % 16) ^ (4 row + blk % 4).
+    constexpr int NA = 2 * MT;
+    const int lrow = lane >> 4;
+    const char* a_ptr[NA];
+    const char* b_ptr[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        if (i < NA) {
+            const int blk = NA * wave + i;
+            const int lc = (lane & 15) ^ ((lrow << 2) | (blk & 3));
+            int ar = min(blk * 4 + lrow, nrows - 1);
+            if (rel) ar = rel[ar];
+            a_ptr[i] = reinterpret_cast<const char*>(A + (size_t)row0 * lda) + (size_t)ar * lda * 2 + lc * 16 + (size_t)s_lo * SKW * 2;
+        }
+        const int lc = (lane & 15) ^ ((lrow << 2) | (i & 3));
+        const int rr = (8 * wave + i) * 4 + lrow;           // row of the 128-row weight tile
+        int col;
+        const uint16_t* base;
+        if (EPI == EPI_SWIGLU) {
+            base = (i >= 4) ? B1 : B0;                      // rows 16 .. 31 of a wave's 32 are the up rows
+            col = n0 + wave * 16 + (rr & 15);
+        } else {
+            base = B0;
+            col = n0 + rr;
+        }
+        b_ptr[i] = reinterpret_cast<const char*>(base) + (size_t)min(col, N - 1) * K * 2 + lc * 16 + (size_t)s_lo * SKW * 2;
+    }
+    auto issue = [&](int t) {                               // stage t of this piece into ring slot t % STAGES
+        const int tc = min(t, ns - 1);                      // past the end: the last stage again, into a slot nobody reads
+        unsigned char* st = lds + (t % G::STAGES) * G::STAGE;
+        const size_t kb = (size_t)tc * SKW * 2;
+#pragma unroll
+        for (int i = 0; i < NA; ++i) {
+            const char* ap = a_ptr[i] + kb;
+            __builtin_amdgcn_global_load_lds(ap, (__attribute__((address_space(3))) void*)(st + (NA * wave + i) * 1024), 16, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const char* bp = b_ptr[i] + kb;
+            __builtin_amdgcn_global_load_lds(bp, (__attribute__((address_space(3))) void*)(st + G::A_BYTES + (8 * wave + i) * 1024), 16, 0, 0);
+        }
+    };
+
+    f32x16 acc[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+
+#pragma unroll
+    for (int t = 0; t < G::STAGES - 1; ++t) issue(t);
+    const int fr = lane & 31, fk = lane >> 5;
+    for (int t = 0; t < ns; ++t) {
+        // LOADS loads per stage and wave; stages t .. t + STAGES - 2 are outstanding: stage t has landed when at
+        // most (STAGES - 2) * LOADS remain: 12 (MT = 2: three stages of 12) or 20 (MT = 1: four stages of 10)
+        if (MT == 2) __builtin_amdgcn_s_waitcnt(0x0F7C);    // vmcnt(12)
+        else __builtin_amdgcn_s_waitcnt(0x4F74);            // vmcnt(20): low four bits 4, high two bits 1
+        __builtin_amdgcn_s_barrier();                       // everybody's part of stage t is in LDS; the slot of stage t - 1 is free
+        issue(t + G::STAGES - 1);
+        const unsigned char* st = lds + (t % G::STAGES) * G::STAGE;
+#pragma unroll
+        for (int s2 = 0; s2 < SKW / 16; ++s2) {
+            const bf16x8 bfr = *reinterpret_cast<const bf16x8*>(st + G::A_BYTES + skinny_off(wave * 32 + fr, 2 * s2 + fk));
+#pragma unroll
+            for (int i = 0; i < MT; ++i) {
+                const bf16x8 af = *reinterpret_cast<const bf16x8*>(st + skinny_off(i * 32 + fr, 2 * s2 + fk));
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr, af, acc[i], 0, 0, 0);
+            }
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0070);                      // no load may still be on its way to LDS when the block ends
+    if (plan.parts > 1) {
+        f32x4* dst = reinterpret_cast<f32x4*>(reinterpret_cast<char*>(partial) + ((size_t)tile_id * plan.parts + piece) * G::PARTIAL);
+#pragma unroll
+        for (int i = 0; i < MT; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                dst[(i * 4 + q) * 256 + tid] = f32x4{acc[i][4 * q], acc[i][4 * q + 1], acc[i][4 * q + 2], acc[i][4 * q + 3]};
+        return;
+    }
+    skinny_store<EPI, MT>(acc, wave, lane, row0, nrows, rel, n0, N, C, ldc);
+}
+
+// Adds the pieces of a tile in piece order (a block per tile, a thread per lane of the GEMM block) and finishes it.
+template <int EPI, int MT>
+__global__ __launch_bounds__(256) void gemm_bf16_skinny_sum_kernel(TileMap m, int N, int K, uint16_t* __restrict__ C, int ldc,
+                                                                   int tiles_n, int ncu, const float* __restrict__ partial) {
+    constexpr int NOUT = (EPI == EPI_SWIGLU) ? SBN / 2 : SBN;
+    const int n_tiles_m = *m.n_tiles;
+    const int total = n_tiles_m * tiles_n;
+    const SkinnyPlan plan = plan_skinny(total, ncu, K / SKW);
+    const int tile_id = blockIdx.x;
+    if (plan.parts < 2 || tile_id >= total) return;
+    const int tile_m = tile_id % n_tiles_m, tile_n = tile_id / n_tiles_m;
+    const int row0 = m.row0[tile_m], nrows = m.nrows[tile_m];
+    const int32_t* rel = m.gather[tile_m] ? m.rel + (size_t)tile_m * kRelPitch : nullptr;
+    const int tid = threadIdx.x;
+    using G = SkinnyGeom<MT>;
+    const f32x4* src = reinterpret_cast<const f32x4*>(reinterpret_cast<const char*>(partial) + (size_t)tile_id * plan.parts * G::PARTIAL) + tid;
+    f32x4 sum[4 * MT];
+#pragma unroll
+    for (int q = 0; q < 4 * MT; ++q) sum[q] = src[q * 256];
+    for (int p = 1; p < plan.parts; ++p) {
+        f32x4 v[4 * MT];
+#pragma unroll
+        for (int q = 0; q < 4 * MT; ++q) v[q] = src[(size_t)p * (G::PARTIAL / 16) + q * 256];
+#pragma unroll
+        for (int q = 0; q < 4 * MT; ++q) sum[q] += v[q];
+    }
+    f32x16 acc[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc[i][4 * q + t] = sum[i * 4 + q][t];
+    skinny_store<EPI, MT>(acc, tid >> 6, tid & 63, row0, nrows, rel, tile_n * NOUT, N, C, ldc);
+}
+
 constexpr int kMaxCU = 256;                    // tail pieces per launch, at most: sizes the partial-tile workspace
 
 // number of CUs of the current device (a round of the grid), at most kMaxCU
@@ -963,6 +1195,42 @@ int launch_bf16(const void* A, int lda, const TileMap& m, const ExpertTable& tab
                        reinterpret_cast<uint16_t*>(C), ldc, tiles_n, ncu, partial);
     MOE_LAUNCH_CHECK("gemm_bf16_tail_kernel");
     return MOE_OK;
+}
+
+// Shares of at most kSkinnyRows rows (the tile map is then made of 32 MT-row tiles).
+inline int skinny_tile_rows(int R) { return R <= 32 ? 32 : 64; }
+template <int EPI, int MT>
+int launch_bf16_skinny_mt(const void* A, int lda, const TileMap& m, const ExpertTable& tab, int which0, int which1, int N, int K,
+                          void* C, int ldc, int R, int nseg, float* partial, hipStream_t st) {
+    using G = SkinnyGeom<MT>;
+    const int nout = (EPI == EPI_SWIGLU) ? SBN / 2 : SBN;
+    const int tiles_n = (N + nout - 1) / nout;
+    const int max_total = ((R + G::BM_ - 1) / G::BM_ + nseg) * tiles_n;
+    const int ncu = round_size();
+    static bool attr_done = false;
+    if (!attr_done) {
+        MOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_skinny_kernel<EPI, MT>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, G::LDS));
+        attr_done = true;
+    }
+    // a tile count below the CU count is multiplied by its pieces up to at most ncu blocks
+    hipLaunchKernelGGL((gemm_bf16_skinny_kernel<EPI, MT>), dim3(std::max(max_total, ncu)), dim3(256), G::LDS, st,
+                       reinterpret_cast<const uint16_t*>(A), lda, m, tab, which0, which1, N, K,
+                       reinterpret_cast<uint16_t*>(C), ldc, tiles_n, ncu, partial);
+    MOE_LAUNCH_CHECK("gemm_bf16_skinny_kernel");
+    // with more than ncu / 2 tiles along N alone no tile is ever cut (plan_skinny): nothing to add up
+    if (2 * tiles_n <= ncu) {
+        hipLaunchKernelGGL((gemm_bf16_skinny_sum_kernel<EPI, MT>), dim3(std::min(max_total, ncu)), dim3(256), 0, st, m, N, K,
+                           reinterpret_cast<uint16_t*>(C), ldc, tiles_n, ncu, partial);
+        MOE_LAUNCH_CHECK("gemm_bf16_skinny_sum_kernel");
+    }
+    return MOE_OK;
+}
+template <int EPI>
+int launch_bf16_skinny(const void* A, int lda, const TileMap& m, const ExpertTable& tab, int which0, int which1, int N, int K,
+                       void* C, int ldc, int R, int nseg, float* partial, hipStream_t st) {
+    if (skinny_tile_rows(R) == 32) return launch_bf16_skinny_mt<EPI, 1>(A, lda, m, tab, which0, which1, N, K, C, ldc, R, nseg, partial, st);
+    return launch_bf16_skinny_mt<EPI, 2>(A, lda, m, tab, which0, which1, N, K, C, ldc, R, nseg, partial, st);
 }
 
 template <int EPI>
@@ -1123,7 +1391,8 @@ static int ffn_impl(const void* recv, int32_t R, const int32_t* seg_offset, cons
     TileMap m = tilemap_at(workspace, R);
     void* hmid = reinterpret_cast<char*>(workspace) + tilemap_bytes(R);
     float* partial = reinterpret_cast<float*>(reinterpret_cast<char*>(hmid) + align256((size_t)R * F * elem_size(dtype)));
-    const int bm = (dtype == MOE_BF16) ? BM : 64;
+    const bool skinny = dtype == MOE_BF16 && R <= kSkinnyRows;
+    const int bm = skinny ? skinny_tile_rows(R) : (dtype == MOE_BF16) ? BM : 64;
     if (ev) MOE_HIP(hipEventRecord(ev[0], st));
     // gathered tiles address their rows by 32-bit byte offsets from the tile's first row
     const int gather = (dtype == MOE_BF16 && (size_t)R * (size_t)std::max(H, F) * 2 <= 0xFFFFFFFFull) ? 1 : 0;
@@ -1136,7 +1405,14 @@ static int ffn_impl(const void* recv, int32_t R, const int32_t* seg_offset, cons
     MOE_LAUNCH_CHECK("tilemap_kernel");
     if (ev) MOE_HIP(hipEventRecord(ev[1], st));
     int rc;
-    if (dtype == MOE_BF16) {
+    if (skinny) {
+        if (act == MOE_ACT_SWIGLU) rc = launch_bf16_skinny<EPI_SWIGLU>(recv, H, m, tab, 0, 1, F, H, hmid, F, R, nseg, partial, st);
+        else if (act == MOE_ACT_GELU_MLP) rc = launch_bf16_skinny<EPI_GELU>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, partial, st);
+        else rc = launch_bf16_skinny<EPI_SILU>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, partial, st);
+        if (rc != MOE_OK) return rc;
+        if (ev) MOE_HIP(hipEventRecord(ev[2], st));
+        rc = launch_bf16_skinny<EPI_PLAIN>(hmid, F, m, tab, 2, 2, H, F, out, H, R, nseg, partial, st);
+    } else if (dtype == MOE_BF16) {
         if (act == MOE_ACT_SWIGLU) rc = launch_bf16<EPI_SWIGLU>(recv, H, m, tab, 0, 1, F, H, hmid, F, R, nseg, partial, st);
         else if (act == MOE_ACT_GELU_MLP) rc = launch_bf16<EPI_GELU>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, partial, st);
         else rc = launch_bf16<EPI_SILU>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, partial, st);

@@ -321,6 +321,17 @@ FFN_CASES = [
     ("bf16", 0, 900, 2048, 2304, 2, 31),                   # with pieces along K as well
     ("bf16", 2, 3000, 256, 256, 64, 1024),                 # the limits: 64 local experts, 1024 segments (many of them empty)
     ("bf16", 1, 5000, 128, 256, 32, 300),
+    # shares of at most 64 rows: the weight-streaming kernels (64-row tiles, tiles cut along K when they are few)
+    ("bf16", 2, 16, 2048, 2048, 1, 1),
+    ("bf16", 2, 64, 1024, 1408, 2, 3),
+    ("bf16", 1, 33, 512, 768, 1, 1),                       # GELU, one row past a 32-row MFMA tile
+    ("bf16", 0, 64, 2048, 2304, 3, 9),                     # gathered tiles
+    ("bf16", 2, 60, 4096, 1536, 4, 40),                    # more segments than rows in most tiles
+    ("bf16", 2, 64, 256, 128, 64, 64),                     # one row per segment, 64 local experts: 64 tiles of one row
+    ("bf16", 1, 50, 128, 12800, 2, 2),                     # 100 stages of K in the second GEMM, many pieces
+    # just past that path
+    ("bf16", 1, 65, 512, 768, 1, 1),
+    ("bf16", 2, 250, 256, 128, 64, 250),
 ]
 
 
