@@ -929,17 +929,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_tail_kernel(TileMap m, int N, i
 
 // ------------------------------------------------------------------------------------------------
 // Shares of at most 64 rows (decode-sized).  The FLOPs are negligible and every weight is used once: the job
-// is to stream the weights at HBM speed.  The big kernel does that at a third of HBM speed, for two reasons
-// that its compute-bound design does not care about: it keeps only 32 KB of weight loads outstanding per CU
-// (the other half of its ring is the mostly empty 256-row A tile), and it reads a weight row 64 bytes at a
-// time, one visit to a DRAM page per 64 bytes.  Here a tile is 64 rows x 128 weight rows and a stage of the
-// LDS ring is 128 elements of K: a wave-load fetches 4 rows x 256 contiguous bytes, a stage is 16 KB of A and
-// 32 KB of weights, three stages fit and two of them (64 KB of weights) are always in flight.  Wave w owns
-// weight rows 32 w .. 32 w + 31 of the tile (SwiGLU: 16 gate rows, then the 16 up rows of the same output
-// columns) and all 64 rows of A: 2 x 1 tiles of v_mfma_f32_32x32x16_bf16, eight k-steps per stage.  A wave
-// loads the weight rows it reads itself; the A tile is shared (one barrier per stage).  With fewer tiles than
-// CUs every tile is cut along K into `parts` pieces (fp32 partial tiles, added in piece order by a second
-// kernel: results do not depend on the run).
+// is to stream the weights at HBM speed, which takes bytes in flight.  The big kernel keeps only 32 KB of
+// weight loads outstanding per CU (the other half of its ring is the mostly empty 256-row A tile) and streams
+// at a third of HBM speed.  Here a tile is 32 or 64 rows x 128 weight rows and a stage of the LDS ring is 128
+// elements of K: a wave-load fetches 4 rows x 256 contiguous bytes, a stage is 8 or 16 KB of A and 32 KB of
+// weights, four or three stages fit and all but one of them (96 or 64 KB of weights) are always in flight.
+// Wave w owns weight rows 32 w .. 32 w + 31 of the tile (SwiGLU: 16 gate rows, then the 16 up rows of the
+// same output columns) and all rows of A: MT x 1 tiles of v_mfma_f32_32x32x16_bf16, eight k-steps per stage.
+// A wave loads the weight rows it reads itself; the A tile is shared (one barrier per stage).  With fewer
+// tiles than CUs every tile is cut along K into `parts` pieces (fp32 partial tiles, added in piece order by a
+// second kernel: results do not depend on the run).
 //
 // LDS layout of a stage: blocks of 1 KB = 4 rows x 16 chunks of 16 bytes, filled by ONE wave-wide
 // direct-to-LDS load (lane l fills slot l).  Inside a block slot(r, c) = 16 r + (c ^ (4 r + blk % 4)):
