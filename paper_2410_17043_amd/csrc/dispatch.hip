@@ -4,7 +4,8 @@
 // Both rest on one stable counting sort of the T*k slots by expert, done without
 // atomics so the permutation is the same on every run.
 //
-// Rank pass (moe_traffic, or moe_dispatch when no fresh ranks are cached in the context):
+// Rank pass (moe_traffic; moe_dispatch runs it too unless the caller has switched rank reuse on and the
+// traffic call on the same indices came directly before):
 //   every slot gets its rank among the slots of its expert, in slot order, plus the
 //   per-expert totals.  Up to 16384 slots this is ONE block of 16 waves (a launch costs
 //   more than the whole count at that size); beyond, three kernels:
@@ -13,12 +14,12 @@
 //     rank_kernel    the same ballots again: block prefix + rank inside the block
 //   The capacity rule, the traffic row and the drop count follow from the totals.
 //
-// Scatter (moe_dispatch): one kernel, one wave per token.  Every block first turns the
-// per-expert totals into segment starts for the requested destination order (a 256-wide
-// prefix sum), then each wave computes the send rows of its token's slots from the cached
-// ranks, writes slot_to_row / row_to_slot, reads the token row once and writes it to the
-// rows of its kept slots (16-byte lanes, 1 KB per wave access, a whole 8 KB row in flight per wave,
-//   cacheable loads - the gate has just read x - and streaming stores).
+// Scatter (moe_dispatch): one kernel.  Every wave first turns the per-expert totals into segment
+// starts for the requested destination order (a prefix sum over the send-order positions), computes the
+// send rows of its tokens' slots from the ranks, writes slot_to_row / row_to_slot, reads its 8 KB of
+// token rows once (one long row or a piece of it, or several short rows) and writes them to the rows of
+// the kept slots (16-byte lanes, 1 KB per wave access, all 8 loads in flight before the first store,
+// cacheable loads - the gate has just read x - and streaming stores).
 #include "common.h"
 #include <algorithm>
 #include <mutex>
