@@ -459,6 +459,8 @@ struct ChunkTables {                  // device pointers
     const int32_t* p_chunk;           // [np] chunk ids grouped by destination, in plan order inside a group
     const int32_t* p_cumhi;           // [np] c_cumhi of p_chunk
     const int32_t* p_begin;           // [G+1] group of destination d is [p_begin[d], p_begin[d+1])
+    const int32_t* d_exp;             // [E] the experts of every destination, ascending: d_exp[d_beg[d] .. d_beg[d+1])
+    const int32_t* d_beg;             // [G+1]
     int32_t* c_row0;                  // [nc+1] written per dispatch: first send row of each chunk
     int32_t* expert_first;            // [E] written per dispatch: position of the expert's first slot in its destination's sequence
 };
@@ -493,29 +495,23 @@ __global__ __launch_bounds__(kLayoutThreads) void chunk_layout_kernel(ChunkTable
                                                                       int32_t* __restrict__ piece_expert,
                                                                       int32_t* __restrict__ n_pieces) {
     __shared__ int kept[MOE_MAX_E], first[MOE_MAX_E], dest_cnt[MOE_MAX_G], wave_tot[kLayoutThreads / 64];
-    __shared__ int d_exp[MOE_MAX_E], d_beg[MOE_MAX_G + 1];    // the experts of every destination, ascending: d_exp[d_beg[d] .. d_beg[d+1])
+    __shared__ int d_exp[MOE_MAX_E], d_beg[MOE_MAX_G + 1];    // the plan's tables (which expert lives where), in LDS
     const int tid = threadIdx.x;
     if (tid < E) {
         const int c = raw_count[tid];
         kept[tid] = (capacity > 0 && c > capacity) ? capacity : c;
+        d_exp[tid] = tb.d_exp[tid];
     }
-    if (tid < G) {
-        int n = 0;
-        for (int e = 0; e < E; ++e) n += (map.expert_gpu[e] == tid) ? 1 : 0;
-        dest_cnt[tid] = n;                                    // for now: experts of the destination
-    }
+    if (tid <= G) d_beg[tid] = tb.d_beg[tid];
     __syncthreads();
-    if (tid == 0) {
+    if (tid < G) {                                            // thread d walks the experts of destination d in id order
         int run = 0;
-        for (int d = 0; d < G; ++d) { d_beg[d] = run; run += dest_cnt[d]; }
-        d_beg[G] = run;
-    }
-    __syncthreads();
-    if (tid < G) {                                            // thread d lists the experts of destination d in id order
-        int at = d_beg[tid], run = 0;
-        for (int e = 0; e < E; ++e)
-            if (map.expert_gpu[e] == tid) { d_exp[at++] = e; first[e] = run; run += kept[e]; }
-        dest_cnt[tid] = run;                                  // from here on: kept slots of the destination
+        for (int i = d_beg[tid]; i < d_beg[tid + 1]; ++i) {
+            const int e = d_exp[i];
+            first[e] = run;
+            run += kept[e];
+        }
+        dest_cnt[tid] = run;                                  // kept slots of the destination
     }
     __syncthreads();
     if (tid < E) tb.expert_first[tid] = first[tid];
@@ -834,13 +830,21 @@ extern "C" int moe_chunk_plan_create(moe_ctx* ctx, const int32_t* expert_to_gpu,
     }
     p_begin[G] = (int32_t)p_chunk.size();
     const int np = (int)p_chunk.size();
-    // device layout: c_dest | c_cumlo | c_cumhi | p_chunk | p_cumhi | p_begin | c_row0 | expert_first
-    const size_t n_static = (size_t)3 * nc + 2 * np + (G + 1);
+    std::vector<int32_t> d_exp, d_beg(G + 1);                // which experts live on each destination
+    for (int d = 0; d < G; ++d) {
+        d_beg[d] = (int32_t)d_exp.size();
+        for (int e = 0; e < s.E; ++e)
+            if (expert_to_gpu[e] == d) d_exp.push_back(e);
+    }
+    d_beg[G] = (int32_t)d_exp.size();                         // = E: build_segmap has checked every expert's GPU
+    // device layout: c_dest | c_cumlo | c_cumhi | p_chunk | p_cumhi | p_begin | d_exp | d_beg | c_row0 | expert_first
+    const size_t n_static = (size_t)3 * nc + 2 * np + (G + 1) + s.E + (G + 1);
     const size_t n_all = n_static + (nc + 1) + s.E;
     std::vector<int32_t> host(n_static);
     size_t o = 0;
     auto put = [&](const std::vector<int32_t>& v, size_t n) { std::copy(v.begin(), v.begin() + n, host.begin() + o); o += n; };
     put(c_dest, nc); put(c_cumlo, nc); put(c_cumhi, nc); put(p_chunk, np); put(p_cumhi, np); put(p_begin, G + 1);
+    put(d_exp, s.E); put(d_beg, G + 1);
     hipError_t e = hipMalloc((void**)&p->dev, n_all * sizeof(int32_t));
     if (e != hipSuccess) {
         delete p;
@@ -860,6 +864,8 @@ extern "C" int moe_chunk_plan_create(moe_ctx* ctx, const int32_t* expert_to_gpu,
     p->tb.p_chunk = d; d += np;
     p->tb.p_cumhi = d; d += np;
     p->tb.p_begin = d; d += G + 1;
+    p->tb.d_exp = d; d += s.E;
+    p->tb.d_beg = d; d += G + 1;
     p->tb.c_row0 = d; d += nc + 1;
     p->tb.expert_first = d;
     p->E = s.E; p->G = G; p->n_chunks = n_chunks;
