@@ -33,7 +33,10 @@ def cases():
 
 def main():
     out = ["# D (rows separated by /) | B (- = all 1) | b_max | brute-force best | simulate(alg1 order) | send_order time",
-           "# exact rationals; written by tests/golden/make_order_ratios.py from the oracle alone"]
+           "# exact rationals; written by tests/golden/make_order_ratios.py from the oracle alone",
+           "# b_max: Theorem 2 (Sec. 4.2) and, with unequal rates, Theorem 4 / Appendix B (Sec. 5.2); the orders: Algorithm 1",
+           "# (Sec. 4.2) and the send order chosen among whole-flow candidates; best: exhaustion over all ((n-1)!)^n orders",
+           "# under the fluid big-switch model of Sec. 3"]
     for D, B in cases():
         best, _ = S.brute_force_best_order(D, B)
         a = S.simulate(D, B, S.alg1_order(D, B)["dest_order"])
