@@ -476,12 +476,42 @@ def measure_stages(torch, wl, cfg, reps):
         rate["shared_ffn_TFLOPs"] = 2.0 * (n_up + 1) * T * H * F * cfg.n_shared / (stage_ms["shared_ffn"] * 1e-3) / 1e12
     if cfg.dtype == "bf16":
         rate["decode_share"] = decode_share(torch, wl, cfg, reps)
+        rate["route_phases_us"] = route_phases(torch, wl, cfg)
     achieved = flops_gemm1 / (gemm_ms[1] * 1e-3) / 1e12
     roof = {"kernel": "gemm_bf16_kernel<%s> (first FFN GEMM with the activation)" % {0: "SiLU", 1: "GELU", 2: "SwiGLU"}[cfg.act],
             "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
             "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None, "launch_ms": float(gemm_ms[1]),
             "flops_per_launch": flops_gemm1}
     return stage_ms, rate, roof
+
+
+def route_phases(torch, wl, cfg, calls=20):
+    """Where the gate kernel's time goes, from the library's timed instantiation of it (moe_diag_route_phases;
+    not the kernel the step runs): microseconds from the first block's start to each phase boundary, median
+    over the waves of all blocks of the last of `calls` back-to-back calls, and the latest end."""
+    import paper_2410_17043_amd as P
+    ctx, x, wg, bias = wl["keep"][0], wl["keep"][1], wl["keep"][2], wl["keep"][3]
+    marks = torch.zeros((cfg.T // 16 + 1) * 128, dtype=torch.int64, device=x.device)
+    idx, w = torch.empty_like(wl["idx"]), torch.empty_like(wl["w"])
+    tpb = 0
+    for _ in range(calls):
+        marks.zero_()
+        tpb = P.moe_diag_route_phases(ctx, x, wg, bias, idx, w, marks)
+    torch.cuda.synchronize()
+    if tpb == 0:
+        return None
+    nb = (cfg.T + tpb - 1) // tpb
+    a = marks[:nb * 128].cpu().numpy().reshape(nb, 16, 8)
+    used = a[:, :, 0] > 0                                     # waves that exist
+    t0 = a[:, :, 0][used].min()
+    rel = (a[:, :, :6] - t0) * 0.01                           # the wall clock ticks at 100 MHz
+    rel[:, :, 5] = np.where(a[:, :, 5] == 0, rel[:, :, 4], rel[:, :, 5])
+    names = ["start", "own_loop_done", "all_waves_done", "tiles_added", "selected", "end"]
+    out = {n: round(float(np.median(rel[:, :, i][used])), 2) for i, n in enumerate(names)}
+    out["end_max"] = round(float(rel[:, :, 5][used].max()), 2)
+    out["tokens_evaluated_again"] = int(a[:, 0, 6].sum())
+    out["tokens_per_block"] = tpb
+    return out
 
 
 def decode_share(torch, wl, cfg, reps, rows=32):

@@ -266,6 +266,16 @@ int moe_selfcheck_tile_map(const int32_t* seg_offset, const int32_t* seg_expert,
  * moe_diag_copy_1r2w: dst0 = dst1 = src, `bytes` (a multiple of 16) read once and written twice with 16-byte
  * accesses, a wave per 8 KB: the traffic shape of a top-2 send buffer without any indexing.  The kernel is
  * launched `reps` times (1..1000) back to back between the two events; ms_out is the average per launch. */
+/* moe_route with the 100 MHz wall clock read at the phase boundaries of the bf16 kernel (the ordinary kernel
+ * contains none of this).  marks: DEVICE, marks_len >= (T / 16 + 1) * 128 elements, zeroed by the caller; on return
+ * (after the stream has been synchronised) marks[(b * 16 + w) * 8 + i] is the clock of wave w of block b at
+ * boundary i: 0 start, 1 its part of the streaming loop done, 2 all waves done, 3 partial tiles added,
+ * 4 selected, 5 end (0 for a block that had no token to evaluate again: it ends at 4); marks[b * 128 + 6] = tokens
+ * that block evaluated again.  *tokens_per_block (HOST) = tokens per block, i.e. ceil(T / that) blocks; 0 when the
+ * shape takes the fp64 kernel, which writes no marks.  Outputs as moe_route.  MOE_ESHAPE when marks is too short. */
+int moe_diag_route_phases(moe_ctx* ctx, const void* x, const void* Wg, const float* gate_bias, int32_t* topk_idx,
+                          float* topk_w, int64_t* marks, size_t marks_len, int32_t* tokens_per_block, void* stream);
+
 /* moe_diag_mfma_run_sum: what the gate's fast pass builds on, exposed so that a test can hold the hardware to
  * the error model the gate assumes: d[t][i][j] = a chain of `run` v_mfma_f32_16x16x32_bf16, the first with a
  * zero accumulator, i.e. the sum over k < 32 run of the exact products a[t][i][k] * b[t][j][k] as the matrix core

@@ -54,6 +54,7 @@ SIGNATURES = {
     "moe_combine": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "moe_diag_mfma_run_sum": (C.c_int, [_vp, _vp, _vp, _i32, _i32, _vp]),
     "moe_diag_mfma_only": (C.c_int, [_i32, _i32, _vp, _vp, C.POINTER(C.c_float), C.POINTER(C.c_double)]),
+    "moe_diag_route_phases": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, C.c_size_t, C.POINTER(C.c_int32), _vp]),
     "moe_diag_copy_1r2w": (C.c_int, [_vp, _vp, _vp, _sz, _i32, _vp, C.POINTER(C.c_float)]),
     "moe_selfcheck_tile_order": (C.c_int, [_i32, _i32, _i32, _i32]),
     "moe_selfcheck_tile_map": (C.c_int, [_pi32, _pi32, _i32, _i32, _i32, _i32, _i32]),

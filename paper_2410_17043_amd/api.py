@@ -251,6 +251,14 @@ def moe_diag_mfma_run_sum(a, b, d):
                                                                        _stream()))
 
 
+def moe_diag_route_phases(ctx, x, w_gate, gate_bias, topk_idx, topk_w, marks):
+    """moe_route with clock marks (see the header); `marks` is a zeroed int64 device tensor.  Returns tokens per block."""
+    tpb = C.c_int32()
+    _check("moe_diag_route_phases", ctx.lib.moe_diag_route_phases(ctx.handle, _ptr(x), _ptr(w_gate), _ptr(gate_bias), _ptr(topk_idx),
+                                                                   _ptr(topk_w), _ptr(marks), marks.numel(), C.byref(tpb), _stream()))
+    return tpb.value
+
+
 def moe_diag_mfma_only(n_blocks, iters, sink):
     """Register-only MFMA loop; returns (milliseconds, floating-point operations issued).  Synchronises."""
     ms, flop = C.c_float(), C.c_double()

@@ -246,11 +246,23 @@ __device__ __forceinline__ bool select_group(const double* __restrict__ zr, int 
 // experts each (L * NC >= E per pass of the selection, L chosen so that the block's threads cover its tokens once).
 // The S waves of a block split the hidden dimension; a wave stages its own pieces (no block barrier in
 // the loop) and keeps MT x NT partial tiles in fp64; partial tiles are added in wave order through LDS.
-template <int NT, int MT, int R, int RUN, int NC, int L, int MAXT>
+//
+// TIMED (diagnostics, moe_diag_route_phases): the same kernel with the 100 MHz wall clock read by lane 0 of every wave
+// at the phase boundaries into marks[block][wave (16)][8]: 0 start, 1 own part of the loop done, 2 all waves
+// done, 3 partial tiles added, 4 selected, 5 end (left untouched by a block with nothing to evaluate again);
+// [block][0][6] = tokens evaluated again.  The ordinary instantiation contains none of it.
+template <int NT, int MT, int R, int RUN, int NC, int L, int MAXT, bool TIMED>
 __global__ __launch_bounds__(MAXT) void route_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ wg,
                                                           const float* __restrict__ bias, int T, int H, int E, int k, int renorm,
-                                                          int32_t* __restrict__ topk_idx, float* __restrict__ topk_w) {
+                                                          int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+                                                          long long* __restrict__ marks) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+#define MOE_MARK(i)                                                                                                      \
+    do {                                                                                                                 \
+        if (TIMED && (threadIdx.x & 63) == 0)                                                                            \
+            marks[((size_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 8 + (i)] = (long long)wall_clock64();                  \
+    } while (0)
+    MOE_MARK(0);
     constexpr int EP = NT * 16, TP = MT * 16, PIECES = MT + NT, kRouteMaxWaves = MAXT / 64;
     const int lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), S = blockDim.x >> 6;
@@ -367,7 +379,9 @@ __global__ __launch_bounds__(MAXT) void route_bf16_kernel(const uint16_t* __rest
             }
             MOE_WAIT_VM(0);                              // no load may still target the ring when it is reused below
         }
+        MOE_MARK(1);
         __syncthreads();
+        MOE_MARK(2);
         // D of the MFMA: lane (r, g) holds rows 4 g + i (tokens), column r (expert), i = 0..3; the diagonal of
         // a (v, v) product (row == column) is therefore in the lanes with r / 4 == g, element r % 4
 #pragma unroll
@@ -415,6 +429,7 @@ __global__ __launch_bounds__(MAXT) void route_bf16_kernel(const uint16_t* __rest
             __syncthreads();
         }
     }
+    MOE_MARK(3);
     // selection: L lanes per token
     const int sub = threadIdx.x & (L - 1);
     for (int tsel = threadIdx.x / L; tsel < TP && tok0 + tsel < T; tsel += blockDim.x / L) {
@@ -437,6 +452,8 @@ __global__ __launch_bounds__(MAXT) void route_bf16_kernel(const uint16_t* __rest
     // pair, the lanes sharing the hidden dimension, lane sums added in a fixed butterfly order - and put in
     // place of the approximate ones; the selection on the patched row is exact.
     const int n_redo = counters[0];
+    MOE_MARK(4);
+    if (TIMED && threadIdx.x == 0) marks[(size_t)blockIdx.x * 16 * 8 + 6] = n_redo;
     if (n_redo == 0) return;                             // block-uniform
     for (int q = threadIdx.x; q < n_redo * E; q += blockDim.x) {
         const int tsel = redo_tok[q / E], e = q % E;
@@ -501,6 +518,8 @@ __global__ __launch_bounds__(MAXT) void route_bf16_kernel(const uint16_t* __rest
         double kth = 0.0;
         select_group<NC, L>(zl + (size_t)tsel * ZP, E, k, renorm, tok0 + tsel, sub, 0.0, selw + tsel * MOE_MAX_K, topk_idx, topk_w, &kth);
     }
+    MOE_MARK(5);
+#undef MOE_MARK
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -616,9 +635,9 @@ int launch_route_mfma(const moe_ctx* c, const void* x, const void* wg, const flo
     return MOE_OK;
 }
 
-template <int NT, int MT, int R, int RUN, int NC, int L, int MAXT>
+template <int NT, int MT, int R, int RUN, int NC, int L, int MAXT, bool TIMED>
 int launch_route_bf16(const moe_ctx* c, const void* x, const void* wg, const float* bias, int32_t* idx, float* w,
-                      hipStream_t st) {
+                      hipStream_t st, long long* marks, int32_t* tokens_per_block) {
     const moe_shape& s = c->s;
     const int ngrp = s.H / 32, TP = MT * 16;
     int S = MAXT / 64;                                    // waves per block: no more than there are groups to share out
@@ -627,14 +646,15 @@ int launch_route_bf16(const moe_ctx* c, const void* x, const void* wg, const flo
                        (size_t)(TP + s.E + TP * MOE_MAX_K) * sizeof(float) + ((size_t)TP + (size_t)TP * s.E + 2) * sizeof(int);
     static bool attr_done = false;
     if (!attr_done) {
-        MOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&route_bf16_kernel<NT, MT, R, RUN, NC, L, MAXT>),
+        MOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&route_bf16_kernel<NT, MT, R, RUN, NC, L, MAXT, TIMED>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
         attr_done = true;
     }
     if (lds > 160 * 1024) return moe_set_error(MOE_EINTERNAL, "moe_route: %zu bytes of LDS", lds);
-    hipLaunchKernelGGL((route_bf16_kernel<NT, MT, R, RUN, NC, L, MAXT>), dim3((s.T + TP - 1) / TP), dim3(64 * S), lds, st,
+    if (tokens_per_block) *tokens_per_block = TP;
+    hipLaunchKernelGGL((route_bf16_kernel<NT, MT, R, RUN, NC, L, MAXT, TIMED>), dim3((s.T + TP - 1) / TP), dim3(64 * S), lds, st,
                        reinterpret_cast<const uint16_t*>(x), reinterpret_cast<const uint16_t*>(wg), bias, s.T, s.H, s.E, s.k,
-                       s.renorm, idx, w);
+                       s.renorm, idx, w, marks);
     MOE_LAUNCH_CHECK("route_bf16_kernel");
     return MOE_OK;
 }
@@ -648,22 +668,25 @@ int route_exact(const moe_ctx* c, const void* x, const void* wg, const float* bi
     return launch_route_mfma<DT, 4, 3>(c, x, wg, bias, idx, w, st);   // E > 64: several passes of 64 experts
 }
 
+// tokens_per_block: where the bf16 kernel says how many tokens a block takes (0: the fp64 kernel ran, no marks)
+template <bool TIMED>
 int route_dispatch(const moe_ctx* c, const void* x, const void* wg, const float* bias, int32_t* idx, float* w,
-                   hipStream_t st) {
+                   hipStream_t st, long long* marks, int32_t* tokens_per_block) {
     const moe_shape& s = c->s;
+    if (tokens_per_block) *tokens_per_block = 0;
     if (s.dtype == MOE_F32) return route_exact<MOE_F32>(c, x, wg, bias, idx, w, st);
     if (s.H % 32 != 0) return route_exact<MOE_BF16>(c, x, wg, bias, idx, w, st);
+#define MOE_ROUTE(...) launch_route_bf16<__VA_ARGS__, TIMED>(c, x, wg, bias, idx, w, st, marks, tokens_per_block)
     // few experts: one token tile per block, 16 waves share the hidden dimension; beyond 64: passes of 64 experts
-    if (s.E <= 16) return launch_route_bf16<1, 1, 4, 1, 1, 16, 1024>(c, x, wg, bias, idx, w, st);
+    if (s.E <= 16) return MOE_ROUTE(1, 1, 4, 1, 1, 16, 1024);
     // up to 64 experts: two token tiles per block and eight waves, two per SIMD, so that one computes while the
     // other waits for its fragments; with many tokens four tiles per block (the gate rows are fetched from L2 once
     // per 64 tokens instead of once per 32) and one wave per SIMD
     const bool few = (s.T + 63) / 64 < 200;
-    if (s.E <= 32) return few ? launch_route_bf16<2, 2, 2, 2, 2, 16, 512>(c, x, wg, bias, idx, w, st)
-                              : launch_route_bf16<2, 4, 3, 2, 8, 4, 256>(c, x, wg, bias, idx, w, st);
-    if (s.E <= 64) return few ? launch_route_bf16<4, 2, 2, 2, 4, 16, 512>(c, x, wg, bias, idx, w, st)
-                              : launch_route_bf16<4, 4, 3, 2, 16, 4, 256>(c, x, wg, bias, idx, w, st);
-    return launch_route_bf16<4, 1, 2, 2, 16, 16, 512>(c, x, wg, bias, idx, w, st);
+    if (s.E <= 32) return few ? MOE_ROUTE(2, 2, 2, 2, 2, 16, 512) : MOE_ROUTE(2, 4, 3, 2, 8, 4, 256);
+    if (s.E <= 64) return few ? MOE_ROUTE(4, 2, 2, 2, 4, 16, 512) : MOE_ROUTE(4, 4, 3, 2, 16, 4, 256);
+    return MOE_ROUTE(4, 1, 2, 2, 16, 16, 512);
+#undef MOE_ROUTE
 }
 
 }  // namespace
@@ -674,5 +697,19 @@ extern "C" int moe_route(moe_ctx* ctx, const void* x, const void* Wg, const floa
     if (!aligned16(x) || !aligned16(Wg)) return moe_set_error(MOE_EALIGN, "moe_route: x and Wg must be 16-byte aligned");
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     ctx->rank_src = nullptr;                             // the indices are about to change: cached slot ranks are stale
-    return route_dispatch(ctx, x, Wg, gate_bias, topk_idx, topk_w, st);
+    return route_dispatch<false>(ctx, x, Wg, gate_bias, topk_idx, topk_w, st, nullptr, nullptr);
+}
+
+extern "C" int moe_diag_route_phases(moe_ctx* ctx, const void* x, const void* Wg, const float* gate_bias, int32_t* topk_idx,
+                                     float* topk_w, int64_t* marks, size_t marks_len, int32_t* tokens_per_block,
+                                     void* stream) {
+    if (!ctx || !x || !Wg || !topk_idx || !topk_w || !marks || !tokens_per_block)
+        return moe_set_error(MOE_EINVAL, "moe_diag_route_phases: NULL argument");
+    if (!aligned16(x) || !aligned16(Wg)) return moe_set_error(MOE_EALIGN, "moe_diag_route_phases: x and Wg must be 16-byte aligned");
+    if (marks_len < ((size_t)ctx->s.T / 16 + 1) * 128)
+        return moe_set_error(MOE_ESHAPE, "moe_diag_route_phases: marks needs (T / 16 + 1) * 128 elements");
+    ctx->rank_src = nullptr;
+    static_assert(sizeof(long long) == sizeof(int64_t), "marks are 64-bit");
+    return route_dispatch<true>(ctx, x, Wg, gate_bias, topk_idx, topk_w, reinterpret_cast<hipStream_t>(stream),
+                                reinterpret_cast<long long*>(marks), tokens_per_block);
 }

@@ -71,6 +71,39 @@ def test_route(H, cfg):
     assert np.max(np.abs(H.host(sh.w) / w_ref - 1.0)) < 1e-5
 
 
+@pytest.mark.parametrize("cfg", [small("c2_mixtral", T=203, H=1024), small("c5_finegrained", T=301, H=512),
+                                 small("c3_switch", T=40, H=1024, E=256, k=16, G=64), small("c1_tiny_fp32", T=37, H=100, E=5, k=3, G=5)],
+                         ids=lambda c: "%s-T%d-E%d-k%d" % (c.name, c.T, c.E, c.k))
+def test_route_phases_diag_gives_the_results_of_moe_route_and_ordered_marks(H, cfg):
+    """The timed instantiation of the gate kernel is the gate kernel: same indices and weights; its clock marks
+    do not go backwards within a wave; a shape that takes the fp64 kernel reports no marks."""
+    inp = route_inputs(cfg)
+    sh = H.Share(cfg)
+    x, wg = H.dev(inp["x"], cfg.dtype), H.dev(inp["w_gate"], cfg.dtype)
+    bias = None if inp["gate_bias"] is None else torch.from_numpy(inp["gate_bias"]).to(H.DEV)
+    sh.route(x, wg, bias)
+    idx2, w2 = torch.full_like(sh.idx, -7), torch.full_like(sh.w, float("nan"))
+    marks = torch.zeros((cfg.T // 16 + 1) * 128, dtype=torch.int64, device=H.DEV)
+    tpb = H.P.moe_diag_route_phases(sh.ctx, x, wg, bias, idx2, w2, marks)
+    torch.cuda.synchronize()
+    assert torch.equal(idx2, sh.idx) and torch.equal(w2, sh.w)
+    if cfg.dtype == "fp32" or cfg.H % 32:
+        assert tpb == 0 and int(marks.abs().sum()) == 0
+        return
+    assert tpb in (16, 32, 64)
+    nb = (cfg.T + tpb - 1) // tpb
+    a = marks[:nb * 128].cpu().numpy().reshape(nb, 16, 8)
+    assert int(np.abs(marks[nb * 128:].cpu().numpy()).sum()) == 0
+    live = a[:, :, 0] > 0
+    assert live[:, 0].all()
+    t = a[:, :, :5]
+    assert (np.diff(t, axis=2)[live] >= 0).all()
+    ends = a[:, :, 5]
+    assert ((ends == 0) | (ends >= a[:, :, 4]))[live].all()
+    with pytest.raises(H.P.MoeError):
+        H.P.moe_diag_route_phases(sh.ctx, x, wg, bias, idx2, w2, marks[:16])
+
+
 def test_route_ties_pick_lower_index(H):
     cfg = small("c2_mixtral", T=96, H=256, E=8, k=3)
     inp = W.make_layer_inputs(cfg)
