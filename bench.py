@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM-side bytes per launch of the first FFN GEMM at c2_mixtral from rocprofv3 counters (FETCH_SIZE x 2.0 +
 # WRITE_SIZE x 1.0, see profiles/bench_c2_mixtral_layer_share.md), valid for the kernel source whose SHA-256
 # starts with the digest below; reported as null as soon as ffn.hip differs from what the counters saw.
-GEMM1_TRAFFIC = {"c2_mixtral": {"bytes": 3.9033e6 * 1024 * 2.0 + 6.6752e5 * 1024, "ffn_hip_sha256": "435f4bea2240b2e1"}}
+GEMM1_TRAFFIC = {"c2_mixtral": {"bytes": 3.9033e6 * 1024 * 2.0 + 6.6752e5 * 1024, "ffn_hip_sha256": "f07c63055353d582"}}
 
 
 def gemm1_traffic_bytes(name):
@@ -223,7 +223,7 @@ def build_workload(cfg, torch, P, W, share="bottleneck", placement=None):
                 shared_out=shared_out, x=x, unit_of_gpu=unit_of_gpu, shared_keep=shared_keep,
                 idx=idx, w=w, expert_count=expert_count, dest_count=dest_count, n_dropped=n_dropped,
                 send_buf=send_buf, slot_to_row=s2r, row_to_slot=r2s, seg_offset=seg_offset, seg_expert=seg_expert,
-                recv=recv, ffn_out=ffn_out, ret=ret, ffn_off=off, ffn_exp=exp, local=local, dest_order=dest_order,
+                recv=recv, ffn_out=ffn_out, ret=ret, ffn_off=off, ffn_exp=exp, ffn_off_dev=ffn_off, ffn_exp_dev=ffn_exp, local=local, dest_order=dest_order,
                 self_spans=self_spans, n_chunks=len(chunks), D=D, rates=rates, plan=plan, keep=(ctx, x, wg, bias, experts, table, ws, chunk_plan))
 
 
@@ -477,6 +477,8 @@ def measure_stages(torch, wl, cfg, reps):
     if cfg.dtype == "bf16":
         rate["decode_share"] = decode_share(torch, wl, cfg, reps)
         rate["route_phases_us"] = route_phases(torch, wl, cfg)
+        if wl["R"] > 64:
+            rate["ffn_tile_phases_us"] = {"gemm1": ffn_tile_phases(torch, wl, cfg, 1), "gemm2": ffn_tile_phases(torch, wl, cfg, 2)}
     achieved = flops_gemm1 / (gemm_ms[1] * 1e-3) / 1e12
     roof = {"kernel": "gemm_bf16_kernel<%s> (first FFN GEMM with the activation)" % {0: "SiLU", 1: "GELU", 2: "SwiGLU"}[cfg.act],
             "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
@@ -512,6 +514,27 @@ def route_phases(torch, wl, cfg, calls=20):
     out["tokens_evaluated_again"] = int(a[:, 0, 6].sum())
     out["tokens_per_block"] = tpb
     return out
+
+
+def ffn_tile_phases(torch, wl, cfg, which, calls=3):
+    """Where the time of a tile of an FFN GEMM goes, from the library's timed instantiation of the GEMM kernel
+    (moe_diag_ffn_phases; not the kernel the step runs): median microseconds per whole tile spent before the loop
+    (first operands on their way), in the loop and after it (activation and stores)."""
+    import paper_2410_17043_amd as P
+    recv, R, table, ws, out = wl["recv"], wl["R"], wl["keep"][5], wl["keep"][6], wl["ffn_out"]
+    off, exp = wl["ffn_off_dev"], wl["ffn_exp_dev"]
+    marks = torch.zeros(P.ffn_phase_marks_len(R, len(wl["ffn_exp"]), cfg.H, cfg.F, cfg.act, which), dtype=torch.int64, device=recv.device)
+    for _ in range(calls):
+        marks.zero_()
+        P.moe_diag_ffn_phases(recv, R, off, exp, len(wl["ffn_exp"]), table, cfg.H, cfg.F, cfg.act, cfg.dtype, out, ws, which, marks)
+    torch.cuda.synchronize()
+    a = marks.cpu().numpy().reshape(-1, 4, 4)[:, 0, :]          # wave 0 of every block
+    a = a[(a[:, 0] > 0) & (a[:, 3] > 0)]
+    nk_whole = (a[:, 2] - a[:, 1])
+    whole = a[nk_whole >= 0.9 * np.median(nk_whole)]              # the pieces of tail tiles have shorter loops
+    d = np.diff(whole, axis=1) * 0.01                             # the wall clock ticks at 100 MHz
+    return {"before_loop": round(float(np.median(d[:, 0])), 2), "loop": round(float(np.median(d[:, 1])), 2),
+            "after_loop": round(float(np.median(d[:, 2])), 2), "tiles": int(len(whole))}
 
 
 def decode_share(torch, wl, cfg, reps, rows=32):

@@ -266,6 +266,18 @@ int moe_selfcheck_tile_map(const int32_t* seg_offset, const int32_t* seg_expert,
  * moe_diag_copy_1r2w: dst0 = dst1 = src, `bytes` (a multiple of 16) read once and written twice with 16-byte
  * accesses, a wave per 8 KB: the traffic shape of a top-2 send buffer without any indexing.  The kernel is
  * launched `reps` times (1..1000) back to back between the two events; ms_out is the average per launch. */
+/* moe_expert_ffn with one of its two GEMMs (which_gemm = 1 or 2) run as a second instantiation of the same kernel
+ * template that reads the 100 MHz wall clock: marks[(b * 4 + w) * 4 + i] (DEVICE, zeroed by the caller) is the
+ * clock of wave w of block b at 0 start, 1 first operands in LDS (loop about to start), 2 loop done, 3 end; a block
+ * that found no tile writes mark 0 only.  marks_len >= (((R + 255) / 256 + nseg) * tiles_n + 256) * 16 elements with
+ * tiles_n = ceil(N / 128) for the first GEMM of a SwiGLU expert (N = F), ceil(F / 256) for the other activations,
+ * ceil(H / 256) for the second GEMM; MOE_ESHAPE otherwise, and for fp32 or shares of at most 64 rows (other
+ * kernels).  Everything else as moe_expert_ffn. */
+int moe_diag_ffn_phases(const void* recv, int32_t R, const int32_t* seg_offset, const int32_t* seg_expert, int32_t nseg,
+                        const moe_expert_w* experts, int32_t n_local, int32_t H, int32_t F, int32_t act, int32_t dtype,
+                        void* out, void* workspace, size_t workspace_bytes, int32_t which_gemm, int64_t* marks,
+                        size_t marks_len, void* stream);
+
 /* moe_route with the 100 MHz wall clock read at the phase boundaries of the bf16 kernel (the ordinary kernel
  * contains none of this).  marks: DEVICE, marks_len >= (T / 16 + 1) * 128 elements, zeroed by the caller; on return
  * (after the stream has been synchronised) marks[(b * 16 + w) * 8 + i] is the clock of wave w of block b at

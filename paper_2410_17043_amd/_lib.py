@@ -51,6 +51,8 @@ SIGNATURES = {
                                  _vp, _vp, _sz, _vp]),
     "moe_expert_ffn_timed": (C.c_int, [_vp, _i32, _vp, _vp, _i32, C.POINTER(moe_expert_w), _i32, _i32, _i32, _i32, _i32,
                                        _vp, _vp, _sz, _vp, C.POINTER(C.c_float)]),
+    "moe_diag_ffn_phases": (C.c_int, [_vp, _i32, _vp, _vp, _i32, C.POINTER(moe_expert_w), _i32, _i32, _i32, _i32, _i32,
+                                      _vp, _vp, _sz, _i32, _vp, _sz, _vp]),
     "moe_combine": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "moe_diag_mfma_run_sum": (C.c_int, [_vp, _vp, _vp, _i32, _i32, _vp]),
     "moe_diag_mfma_only": (C.c_int, [_i32, _i32, _vp, _vp, C.POINTER(C.c_float), C.POINTER(C.c_double)]),

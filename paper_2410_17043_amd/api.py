@@ -240,6 +240,20 @@ def moe_expert_ffn_timed(recv, R, seg_offset, seg_expert, nseg, experts, H, F, a
     return tuple(ms)
 
 
+def ffn_phase_marks_len(R, nseg, H, F, act, which_gemm):
+    tiles_n = -(-F // (128 if act == ACT_SWIGLU else 256)) if which_gemm == 1 else -(-H // 256)
+    return (((R + 255) // 256 + nseg) * tiles_n + 256) * 16
+
+
+def moe_diag_ffn_phases(recv, R, seg_offset, seg_expert, nseg, experts, H, F, act, dtype, out, workspace, which_gemm, marks):
+    """moe_expert_ffn with GEMM `which_gemm` (1 or 2) timed from inside (see the header); `marks` is a zeroed int64
+    device tensor of at least ffn_phase_marks_len(...) elements."""
+    tab = experts if isinstance(experts, C.Array) else expert_table(experts)
+    _check("moe_diag_ffn_phases", _lib.load().moe_diag_ffn_phases(
+        _ptr(recv), R, _ptr(seg_offset), _ptr(seg_expert), nseg, tab, len(tab), H, F, act, _DT[dtype], _ptr(out),
+        _ptr(workspace), workspace.numel() * workspace.element_size(), which_gemm, _ptr(marks), marks.numel(), _stream()))
+
+
 def moe_combine(ctx, ret, slot_to_row, topk_w, shared_out, y):
     _check("moe_combine", ctx.lib.moe_combine(ctx.handle, _ptr(ret), _ptr(slot_to_row), _ptr(topk_w),
                                               _ptr(shared_out), _ptr(y), _stream()))

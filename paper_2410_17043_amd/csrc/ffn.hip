@@ -667,12 +667,22 @@ __device__ __forceinline__ void flush_rows(int i_lo, int i_hi, const unsigned ch
 // The MFMAs are issued as D = B . A^T (operands swapped), so a lane ends up with 4 consecutive
 // output COLUMNS of one row: the epilogue packs them to 8 bytes, transposes through LDS and
 // writes whole 128-byte lines.
-template <int EPI>
+//
+// TIMED (diagnostics, moe_diag_ffn_phases): the same kernel with the 100 MHz wall clock read by lane 0 of every wave
+// into marks[block][wave][4]: 0 start, 1 first operands in LDS (loop about to start), 2 loop done, 3 end.  The
+// ordinary instantiation contains none of it.
+template <int EPI, bool TIMED>
 __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __restrict__ A, int lda, TileMap m,
                                                            ExpertTable tab, int which0, int which1, int N, int K,
                                                            uint16_t* __restrict__ C, int ldc, int tiles_n, int ncu,
-                                                           float* __restrict__ partial) {
+                                                           float* __restrict__ partial, long long* __restrict__ marks) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+#define MOE_MARK(i)                                                                                                 \
+    do {                                                                                                            \
+        if (TIMED && (threadIdx.x & 63) == 0)                                                                       \
+            marks[((size_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 4 + (i)] = (long long)wall_clock64();              \
+    } while (0)
+    MOE_MARK(0);
     constexpr int NOUT = (EPI == EPI_SWIGLU) ? 128 : 256;                  // output columns per block
     const int n_tiles_m = *m.n_tiles;
     const int total = n_tiles_m * tiles_n;
@@ -809,6 +819,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
     bf16x8 a0[4], b0[4], a1[4], b1[4];
     __builtin_amdgcn_s_waitcnt(0x0F7C);            // vmcnt(12): pair (0, 1) is in LDS
     __builtin_amdgcn_s_barrier();
+    MOE_MARK(1);
     load_frags(a0, b0, lds, 0);
 #define MOE_PHASE_SCHED()                                                                      \
     _Pragma("unroll") for (int q = 0; q < 8; ++q) {   /* (MFMA, LDS read) x 8 */                \
@@ -858,6 +869,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
     // no load may still target LDS, and no wave may still read operands, when LDS is reused below
     __builtin_amdgcn_s_waitcnt(0x0070);            // vmcnt(0) lgkmcnt(0)
     __builtin_amdgcn_s_barrier();
+    MOE_MARK(2);
 
     if (piece >= 0) {
         // a piece of a tail tile: the raw accumulators, 16 bytes per lane and store (whole 4 KB per store)
@@ -872,11 +884,14 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
                     const f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
                     dst[((i * 4 + j) * 4 + q) * 256 + tid] = v;
                 }
+        MOE_MARK(3);
         return;
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) stage_rows<EPI>(acc[i], i, lds);
     flush_rows<EPI>(0, 4, lds, row0, nrows, rel, n0, N, C, ldc);
+    MOE_MARK(3);
+#undef MOE_MARK
 }
 
 // Adds the pieces of one 32-row tile per wave (blockIdx.x % 4) of tail tile blockIdx.x / 4 in piece
@@ -1169,9 +1184,10 @@ int round_size() {
     return ncu;
 }
 
-template <int EPI>
+template <int EPI, bool TIMED = false>
 int launch_bf16(const void* A, int lda, const TileMap& m, const ExpertTable& tab, int which0, int which1, int N, int K,
-                void* C, int ldc, int R, int nseg, float* partial, hipStream_t st) {
+                void* C, int ldc, int R, int nseg, float* partial, hipStream_t st, long long* marks = nullptr,
+                size_t marks_len = 0) {
     const int nout = (EPI == EPI_SWIGLU) ? 128 : 256;
     const int tiles_n = (N + nout - 1) / nout;
     const int max_tiles_m = (R + BM - 1) / BM + nseg;
@@ -1179,16 +1195,18 @@ int launch_bf16(const void* A, int lda, const TileMap& m, const ExpertTable& tab
     const size_t lds = (size_t)kLdsBytes;
     static bool attr_done = false;
     if (!attr_done) {
-        MOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<EPI>),
+        MOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_kernel<EPI, TIMED>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         MOE_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_bf16_tail_kernel<EPI>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         attr_done = true;
     }
     // whole tiles first, then at most ncu pieces of tail tiles; blocks past the real tile count exit at once
-    hipLaunchKernelGGL((gemm_bf16_kernel<EPI>), dim3(max_tiles_m * tiles_n + ncu), dim3(256), lds, st,
+    if (TIMED && marks_len < (size_t)(max_tiles_m * tiles_n + ncu) * 16)
+        return moe_set_error(MOE_ESHAPE, "moe_diag_ffn_phases: marks needs %zu elements", (size_t)(max_tiles_m * tiles_n + ncu) * 16);
+    hipLaunchKernelGGL((gemm_bf16_kernel<EPI, TIMED>), dim3(max_tiles_m * tiles_n + ncu), dim3(256), lds, st,
                        reinterpret_cast<const uint16_t*>(A), lda, m, tab, which0, which1, N, K,
-                       reinterpret_cast<uint16_t*>(C), ldc, tiles_n, ncu, partial);
+                       reinterpret_cast<uint16_t*>(C), ldc, tiles_n, ncu, partial, marks);
     MOE_LAUNCH_CHECK("gemm_bf16_kernel");
     hipLaunchKernelGGL((gemm_bf16_tail_kernel<EPI>), dim3(2 * ncu), dim3(256), lds, st, m, N, K,   // ncu / 2 tiles at most, 4 blocks each
                        reinterpret_cast<uint16_t*>(C), ldc, tiles_n, ncu, partial);
@@ -1352,9 +1370,11 @@ extern "C" size_t moe_ffn_workspace_bytes(int32_t R_max, int32_t H, int32_t F, i
     return tilemap_bytes(R_max) + align256((size_t)R_max * F * elem_size(dtype)) + partial + 256;
 }
 
+// timed_gemm: 0 none, 1 / 2: that GEMM runs as its TIMED instantiation and writes marks (bf16, more than 64 rows)
 static int ffn_impl(const void* recv, int32_t R, const int32_t* seg_offset, const int32_t* seg_expert, int32_t nseg,
                     const moe_expert_w* experts, int32_t n_local, int32_t H, int32_t F, int32_t act, int32_t dtype,
-                    void* out, void* workspace, size_t workspace_bytes, hipStream_t st, hipEvent_t* ev) {
+                    void* out, void* workspace, size_t workspace_bytes, hipStream_t st, hipEvent_t* ev,
+                    int timed_gemm = 0, long long* marks = nullptr, size_t marks_len = 0) {
     if (!recv || !seg_offset || !seg_expert || !experts || !out || !workspace)
         return moe_set_error(MOE_EINVAL, "moe_expert_ffn: NULL argument");
     if (R < 0 || nseg < 0 || H <= 0 || F <= 0) return moe_set_error(MOE_EINVAL, "moe_expert_ffn: negative size");
@@ -1391,6 +1411,8 @@ static int ffn_impl(const void* recv, int32_t R, const int32_t* seg_offset, cons
     void* hmid = reinterpret_cast<char*>(workspace) + tilemap_bytes(R);
     float* partial = reinterpret_cast<float*>(reinterpret_cast<char*>(hmid) + align256((size_t)R * F * elem_size(dtype)));
     const bool skinny = dtype == MOE_BF16 && R <= kSkinnyRows;
+    if (timed_gemm != 0 && (dtype != MOE_BF16 || skinny))
+        return moe_set_error(MOE_ESHAPE, "moe_diag_ffn_phases: bf16 and more than %d rows needed", kSkinnyRows);
     const int bm = skinny ? skinny_tile_rows(R) : (dtype == MOE_BF16) ? BM : 64;
     if (ev) MOE_HIP(hipEventRecord(ev[0], st));
     // gathered tiles address their rows by 32-bit byte offsets from the tile's first row
@@ -1412,12 +1434,17 @@ static int ffn_impl(const void* recv, int32_t R, const int32_t* seg_offset, cons
         if (ev) MOE_HIP(hipEventRecord(ev[2], st));
         rc = launch_bf16_skinny<EPI_PLAIN>(hmid, F, m, tab, 2, 2, H, F, out, H, R, nseg, partial, st);
     } else if (dtype == MOE_BF16) {
-        if (act == MOE_ACT_SWIGLU) rc = launch_bf16<EPI_SWIGLU>(recv, H, m, tab, 0, 1, F, H, hmid, F, R, nseg, partial, st);
+        if (timed_gemm == 1) {
+            if (act == MOE_ACT_SWIGLU) rc = launch_bf16<EPI_SWIGLU, true>(recv, H, m, tab, 0, 1, F, H, hmid, F, R, nseg, partial, st, marks, marks_len);
+            else if (act == MOE_ACT_GELU_MLP) rc = launch_bf16<EPI_GELU, true>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, partial, st, marks, marks_len);
+            else rc = launch_bf16<EPI_SILU, true>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, partial, st, marks, marks_len);
+        } else if (act == MOE_ACT_SWIGLU) rc = launch_bf16<EPI_SWIGLU>(recv, H, m, tab, 0, 1, F, H, hmid, F, R, nseg, partial, st);
         else if (act == MOE_ACT_GELU_MLP) rc = launch_bf16<EPI_GELU>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, partial, st);
         else rc = launch_bf16<EPI_SILU>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, partial, st);
         if (rc != MOE_OK) return rc;
         if (ev) MOE_HIP(hipEventRecord(ev[2], st));
-        rc = launch_bf16<EPI_PLAIN>(hmid, F, m, tab, 2, 2, H, F, out, H, R, nseg, partial, st);
+        if (timed_gemm == 2) rc = launch_bf16<EPI_PLAIN, true>(hmid, F, m, tab, 2, 2, H, F, out, H, R, nseg, partial, st, marks, marks_len);
+        else rc = launch_bf16<EPI_PLAIN>(hmid, F, m, tab, 2, 2, H, F, out, H, R, nseg, partial, st);
     } else {
         if (act == MOE_ACT_SWIGLU) rc = launch_f32<EPI_SWIGLU>(recv, H, m, tab, 0, 1, F, H, hmid, F, R, nseg, st);
         else if (act == MOE_ACT_GELU_MLP) rc = launch_f32<EPI_GELU>(recv, H, m, tab, 0, 0, F, H, hmid, F, R, nseg, st);
@@ -1458,4 +1485,16 @@ extern "C" int moe_expert_ffn_timed(const void* recv, int32_t R, const int32_t* 
     for (int i = 0; i < 4; ++i)
         if (ev[i]) (void)hipEventDestroy(ev[i]);
     return rc;
+}
+
+extern "C" int moe_diag_ffn_phases(const void* recv, int32_t R, const int32_t* seg_offset, const int32_t* seg_expert,
+                                   int32_t nseg, const moe_expert_w* experts, int32_t n_local, int32_t H, int32_t F,
+                                   int32_t act, int32_t dtype, void* out, void* workspace, size_t workspace_bytes,
+                                   int32_t which_gemm, int64_t* marks, size_t marks_len, void* stream) {
+    if (!marks || (which_gemm != 1 && which_gemm != 2))
+        return moe_set_error(MOE_EINVAL, "moe_diag_ffn_phases: marks is NULL or which_gemm is not 1 or 2");
+    static_assert(sizeof(long long) == sizeof(int64_t), "marks are 64-bit");
+    return ffn_impl(recv, R, seg_offset, seg_expert, nseg, experts, n_local, H, F, act, dtype, out, workspace,
+                    workspace_bytes, reinterpret_cast<hipStream_t>(stream), nullptr, which_gemm,
+                    reinterpret_cast<long long*>(marks), marks_len);
 }

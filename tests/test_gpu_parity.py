@@ -382,6 +382,41 @@ def test_expert_ffn(H, dtype, act, R, Hd, F, n_local, nseg):
     H.assert_close(got, ref, dtype)
 
 
+@pytest.mark.parametrize("which", [1, 2])
+def test_ffn_phases_diag_gives_the_results_of_moe_expert_ffn_and_ordered_marks(H, which):
+    """The timed instantiation of the GEMM kernel is the GEMM kernel: bitwise the same output; its clock marks do
+    not go backwards; blocks that found no tile stop after the first mark; a share of the streaming kernels is refused."""
+    Hd, F, R, act = 512, 1408, 700, 2
+    cfg = small("c2_mixtral", H=Hd, F=F)
+    r = np.random.default_rng(3)
+    recv = W.round_to_dtype(r.standard_normal((R, Hd)).astype(np.float32), "bf16")
+    experts = [H.weights_to_dev(W.make_expert_weights(cfg, e), "bf16") for e in range(2)]
+    off, exp = make_segments(r, R, 5, 2)
+    x = H.dev(recv, "bf16")
+    ref = H.run_ffn(x, off, exp, experts, Hd, F, act, "bf16")
+    i32 = dict(dtype=torch.int32, device=H.DEV)
+    so, se = torch.tensor(off, **i32), torch.tensor(exp, **i32)
+    ws = torch.empty(H.P.moe_ffn_workspace_bytes(R, Hd, F, act, "bf16"), dtype=torch.uint8, device=H.DEV)
+    out = torch.full_like(ref, float("nan"))
+    marks = torch.zeros(H.P.ffn_phase_marks_len(R, len(exp), Hd, F, act, which), dtype=torch.int64, device=H.DEV)
+    H.P.moe_diag_ffn_phases(x, R, so, se, len(exp), experts, Hd, F, act, "bf16", out, ws, which, marks)
+    torch.cuda.synchronize()
+    rows = np.zeros(R, dtype=bool)
+    for a, b in zip(off[:-1], off[1:]):
+        rows[a:b] = True
+    assert torch.equal(out[torch.from_numpy(rows).to(H.DEV)], ref[torch.from_numpy(rows).to(H.DEV)])
+    a = marks.cpu().numpy().reshape(-1, 4, 4)
+    ran = a[:, 0, 3] > 0                                           # blocks that had a tile (the others stop after mark 0)
+    assert ran.sum() >= 3                                          # a few tiles at least
+    assert (np.diff(a[ran], axis=2) >= 0).all()
+    assert (a[~ran][:, :, 1:] == 0).all()
+    with pytest.raises(H.P.MoeError):
+        H.P.moe_diag_ffn_phases(x, R, so, se, len(exp), experts, Hd, F, act, "bf16", out, ws, which, marks[:64])
+    with pytest.raises(H.P.MoeError):
+        H.P.moe_diag_ffn_phases(x, 40, torch.tensor([0, 40], **i32), torch.tensor([0], **i32), 1, experts, Hd, F, act, "bf16", out, ws,
+                                which, marks)
+
+
 def test_expert_ffn_leaves_rows_outside_segments_untouched(H):
     cfg = small("c2_mixtral", H=128, F=256)
     r = np.random.default_rng(5)
