@@ -171,8 +171,9 @@ template <int L> __device__ __forceinline__ float group_max(float v) {
 
 // Selection for one token by a group of L neighbouring lanes (sub = 0..L-1; lane `sub` looks after experts sub,
 // sub + L, ..., at most NC of them, read once from zr[0..E) in LDS): the k + 1 largest, ties to the lower index;
-// softmax weights; returns whether every gap between consecutive ones exceeds min_gap, and the k-th largest in
-// *kth.  selw: LDS scratch [k] of this token.
+// softmax weights; returns whether every gap between consecutive ones exceeds min_gap (a negative min_gap: only
+// the k largest are extracted and the answer means nothing), and the k-th largest in *kth.  selw: LDS scratch
+// [k] of this token.
 template <int NC, int L>
 __device__ __forceinline__ bool select_group(const double* __restrict__ zr, int E, int k, int renorm, int t, int sub,
                                              double min_gap, float* __restrict__ selw, int32_t* __restrict__ topk_idx,
@@ -184,7 +185,7 @@ __device__ __forceinline__ bool select_group(const double* __restrict__ zr, int 
         live[i] = sub + L * i < E;
         cv[i] = live[i] ? zr[sub + L * i] : 0.0;
     }
-    const int n_take = min(k + 1, E);
+    const int n_take = min(min_gap >= 0.0 ? k + 1 : k, E);   // a negative min_gap: no gaps wanted, the k largest only
     double zmax = 0.0, prev = 0.0;
     float den = 1.f, wsum = 0.f;
     bool safe = true;
@@ -516,7 +517,7 @@ __global__ __launch_bounds__(MAXT) void route_bf16_kernel(const uint16_t* __rest
     for (int f = threadIdx.x / L; f < n_redo; f += blockDim.x / L) {
         const int tsel = redo_tok[f];
         double kth = 0.0;
-        select_group<NC, L>(zl + (size_t)tsel * ZP, E, k, renorm, tok0 + tsel, sub, 0.0, selw + tsel * MOE_MAX_K, topk_idx, topk_w, &kth);
+        select_group<NC, L>(zl + (size_t)tsel * ZP, E, k, renorm, tok0 + tsel, sub, -1.0, selw + tsel * MOE_MAX_K, topk_idx, topk_w, &kth);
     }
     MOE_MARK(5);
 #undef MOE_MARK
