@@ -1208,9 +1208,15 @@ int launch_bf16(const void* A, int lda, const TileMap& m, const ExpertTable& tab
                        reinterpret_cast<const uint16_t*>(A), lda, m, tab, which0, which1, N, K,
                        reinterpret_cast<uint16_t*>(C), ldc, tiles_n, ncu, partial, marks);
     MOE_LAUNCH_CHECK("gemm_bf16_kernel");
-    hipLaunchKernelGGL((gemm_bf16_tail_kernel<EPI>), dim3(2 * ncu), dim3(256), lds, st, m, N, K,   // ncu / 2 tiles at most, 4 blocks each
-                       reinterpret_cast<uint16_t*>(C), ldc, tiles_n, ncu, partial);
-    MOE_LAUNCH_CHECK("gemm_bf16_tail_kernel");
+    // the tile count is only known on the device, but with a short K no count at all gives a tail (plan_tail
+    // wants pieces of a minimum length): then there is nothing to add up and the launch is left out
+    bool tail_possible = false;
+    for (int rem = 1; rem < ncu && !tail_possible; ++rem) tail_possible = plan_tail(rem, ncu, K / BK).n_tail > 0;
+    if (tail_possible) {
+        hipLaunchKernelGGL((gemm_bf16_tail_kernel<EPI>), dim3(2 * ncu), dim3(256), lds, st, m, N, K,   // ncu / 2 tiles at most, 4 blocks each
+                           reinterpret_cast<uint16_t*>(C), ldc, tiles_n, ncu, partial);
+        MOE_LAUNCH_CHECK("gemm_bf16_tail_kernel");
+    }
     return MOE_OK;
 }
 
