@@ -247,6 +247,16 @@ int moe_combine(moe_ctx* ctx, const void* ret, const int32_t* slot_to_row, const
  * moe_status. */
 int moe_selfcheck_tile_order(int32_t tiles_m, int32_t tiles_n, int32_t ncu, int32_t nk);
 
+/* Plan of the weight-streaming FFN kernels (shares of at most 64 rows) for `total` tiles of `ns` stages of K on
+ * ncu compute units: checks that the pieces cover the stages exactly once, are at least two stages long and fit
+ * the launch.  Returns the number of pieces per tile (1 = whole tiles), or a negative moe_status. */
+int moe_selfcheck_skinny_plan(int32_t total, int32_t ncu, int32_t ns);
+
+/* How the scatter kernels share rows of row16 16-byte units among waves for k slots per token: out3 (HOST) =
+ * {tokens per wave, log2 of the 1 KB wave-loads per row when several tokens share a wave, 8 KB pieces per row};
+ * checks that the rows fit a wave's loads, that every slot has a lane and that the pieces cover the row. */
+int moe_selfcheck_row_geometry(int32_t row16, int32_t k, int32_t* out3);
+
 /* Tile map of the FFN for a segment list (HOST seg_offset [nseg+1], seg_expert [nseg]; R rows, tiles of bm
  * rows, n_local experts; gather = chain the segments of an expert into full tiles): runs the steps of the
  * device kernel on the host and checks that every row of every non-empty segment of a known expert lies in

@@ -59,6 +59,8 @@ SIGNATURES = {
     "moe_diag_route_phases": (C.c_int, [_vp, _vp, _vp, _vp, _vp, _vp, _vp, C.c_size_t, C.POINTER(C.c_int32), _vp]),
     "moe_diag_copy_1r2w": (C.c_int, [_vp, _vp, _vp, _sz, _i32, _vp, C.POINTER(C.c_float)]),
     "moe_selfcheck_tile_order": (C.c_int, [_i32, _i32, _i32, _i32]),
+    "moe_selfcheck_skinny_plan": (C.c_int, [_i32, _i32, _i32]),
+    "moe_selfcheck_row_geometry": (C.c_int, [_i32, _i32, _pi32]),
     "moe_selfcheck_tile_map": (C.c_int, [_pi32, _pi32, _i32, _i32, _i32, _i32, _i32]),
     "aurora_order": (C.c_int, [_i32, C.POINTER(C.c_int64), C.POINTER(C.c_double), C.POINTER(aurora_schedule)]),
     "aurora_schedule_free": (None, [C.POINTER(aurora_schedule)]),

@@ -691,6 +691,19 @@ int launch_scatter(const moe_shape& s, const RankScratch& sc, const SegMap& map,
 
 }  // namespace
 
+extern "C" int moe_selfcheck_row_geometry(int32_t row16, int32_t k, int32_t* out3) {
+    if (row16 < 1 || k < 1 || k > MOE_MAX_K || !out3) return moe_set_error(MOE_EINVAL, "moe_selfcheck_row_geometry: bad argument");
+    const RowGeom g = row_geometry(row16, k);
+    out3[0] = g.tpw; out3[1] = g.lsh; out3[2] = g.pieces;
+    // a wave's kRowLoads loads must hold its rows; lane q * k + j must exist; the pieces must cover the row
+    if (g.tpw < 1 || g.pieces < 1 || g.tpw * k > 64) return moe_set_error(MOE_EINTERNAL, "row geometry: %d tokens x %d slots per wave", g.tpw, k);
+    if (g.tpw > 1 && (row16 != (64 << g.lsh) || (g.tpw << g.lsh) > kRowLoads || g.pieces != 1))
+        return moe_set_error(MOE_EINTERNAL, "row geometry: %d rows of %d units do not fit a wave", g.tpw, row16);
+    if ((int64_t)g.pieces * 64 * kRowLoads < row16 || (int64_t)(g.pieces - 1) * 64 * kRowLoads >= row16)
+        return moe_set_error(MOE_EINTERNAL, "row geometry: %d pieces for %d units", g.pieces, row16);
+    return MOE_OK;
+}
+
 extern "C" int moe_traffic(moe_ctx* ctx, const int32_t* topk_idx, const int32_t* expert_to_gpu, int32_t* expert_count,
                            int32_t* dest_count, int32_t* n_dropped, void* stream) {
     if (!ctx || !topk_idx || !expert_to_gpu || !expert_count || !dest_count || !n_dropped)

@@ -1303,6 +1303,18 @@ extern "C" int moe_selfcheck_tile_order(int32_t tiles_m, int32_t tiles_n, int32_
 // segment of a known expert lies in exactly one tile of that expert, that tile rows increase, that exactly
 // the tiles with gaps are marked as gathered and that their offset tables are complete.  Returns the
 // number of tiles, or a negative status.
+extern "C" int moe_selfcheck_skinny_plan(int32_t total, int32_t ncu, int32_t ns) {
+    if (total < 1 || ncu < 1 || ns < 1) return moe_set_error(MOE_EINVAL, "moe_selfcheck_skinny_plan: total, ncu and ns must be positive");
+    const SkinnyPlan p = plan_skinny(total, ncu, ns);
+    // every stage in exactly one piece, no empty piece, no more blocks than max(total, ncu), pieces of at least 2 stages
+    if (p.parts < 1 || p.per < 1 || (int64_t)p.parts * p.per < ns || (int64_t)(p.parts - 1) * p.per >= ns)
+        return moe_set_error(MOE_EINTERNAL, "skinny plan: %d pieces of %d stages do not cover %d stages once", p.parts, p.per, ns);
+    if ((int64_t)total * p.parts > std::max(total, ncu))
+        return moe_set_error(MOE_EINTERNAL, "skinny plan: %d tiles x %d pieces exceed the launch", total, p.parts);
+    if (p.parts > 1 && (p.per < 2 || total >= ncu)) return moe_set_error(MOE_EINTERNAL, "skinny plan: pieces too short or not needed");
+    return p.parts;
+}
+
 extern "C" int moe_selfcheck_tile_map(const int32_t* seg_offset, const int32_t* seg_expert, int32_t nseg, int32_t R,
                                       int32_t bm, int32_t n_local, int32_t gather) {
     if (!seg_offset || !seg_expert || nseg < 0 || nseg > kMaxSeg || R < 0 || bm < 1 || bm > kRelPitch || n_local < 1 || n_local > MOE_MAX_LOCAL)

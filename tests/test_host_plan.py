@@ -369,3 +369,29 @@ def test_tile_map_gathers_the_segments_of_an_expert():
     assert run([10, 10, 10], [0, 1, 0], 2, 256, 1, R=25) == 2
     assert run([1] * 1024, [i % 3 for i in range(1024)], 3, 256, 1) == 2 + 2 + 2
     assert run([1] * 1024, [i % 3 for i in range(1024)], 3, 256, 0) == 1024
+
+
+def test_skinny_plan_and_row_geometry_self_checks():
+    """Host logic of the weight-streaming FFN kernels and of the scatter's row sharing, checked by the library's own
+    invariants over the whole range of shapes, plus the values the five workloads and a decode share get."""
+    import ctypes as C
+    from paper_2410_17043_amd import _lib
+    lib = _lib.load()
+    for total in list(range(1, 70)) + [111, 112, 127, 128, 129, 224, 255, 256, 257, 448, 1000]:
+        for ns in (1, 2, 3, 4, 5, 7, 8, 11, 16, 32, 44, 100, 112, 113):
+            for ncu in (256, 304, 64):
+                parts = lib.moe_selfcheck_skinny_plan(total, ncu, ns)
+                assert parts >= 1, (total, ncu, ns)
+    assert lib.moe_selfcheck_skinny_plan(224, 256, 32) == 1       # first GEMM of a Mixtral-shape expert, 32 rows
+    assert lib.moe_selfcheck_skinny_plan(32, 256, 112) == 8       # second GEMM: K = 14336 in 8 pieces of 14 stages
+    assert lib.moe_selfcheck_skinny_plan(0, 256, 8) < 0
+    out = (C.c_int32 * 3)()
+    for row16 in list(range(1, 600)) + [1024, 1536, 4096, 65536]:
+        for k in (1, 2, 3, 6, 8, 9, 16):
+            assert lib.moe_selfcheck_row_geometry(row16, k, out) == 0, (row16, k, list(out))
+    want = {(512, 2): (1, 1), (128, 1): (4, 1), (256, 2): (2, 1), (256, 6): (1, 1), (64, 2): (8, 1), (64, 6): (2, 1),
+            (1024, 2): (1, 2), (576, 3): (1, 2), (16, 2): (1, 1)}
+    for (row16, k), (tpw, pieces) in want.items():
+        assert lib.moe_selfcheck_row_geometry(row16, k, out) == 0
+        assert (out[0], out[2]) == (tpw, pieces), (row16, k, list(out))
+    assert lib.moe_selfcheck_row_geometry(0, 2, out) < 0 and lib.moe_selfcheck_row_geometry(64, 17, out) < 0
