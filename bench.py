@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 # HBM-side bytes per launch of the first FFN GEMM at c2_mixtral from rocprofv3 counters (FETCH_SIZE x 2.0 +
 # WRITE_SIZE x 1.0, see profiles/bench_c2_mixtral_layer_share.md), valid for the kernel source whose SHA-256
 # starts with the digest below; reported as null as soon as ffn.hip differs from what the counters saw.
-GEMM1_TRAFFIC = {"c2_mixtral": {"bytes": 3.90305e6 * 1024 * 2.0 + 6.6752e5 * 1024, "ffn_hip_sha256": "6ce27ced7aba11a6"}}
+GEMM1_TRAFFIC = {"c2_mixtral": {"bytes": 3.9033e6 * 1024 * 2.0 + 6.6752e5 * 1024, "ffn_hip_sha256": "05411752ca640057"}}
 
 
 def gemm1_traffic_bytes(name):

@@ -724,12 +724,21 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(const uint16_t* __res
     const char* a_base = reinterpret_cast<const char*>(A + (size_t)row0 * lda) + (size_t)kt_lo * BK * 2;
     const char* b_base[4];
     uint32_t a_voff[4], b_voff[4];
+    int a_row[4];                                            // row (relative to row0) of the tile rows this lane fetches
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a_row[i] = min((wave + 4 * i) * 16 + lr, nrows - 1);
+    if (rel) {                                               // gathered tile: offsets from row0, below 2^32 bytes (checked
+        int t[4];                                            // on the host); the four loads go out together
+#pragma unroll
+        for (int i = 0; i < 4; ++i) t[i] = rel[a_row[i]];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a_row[i] = t[i];
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int blk = wave + 4 * i;                        // 16-row block of the tile (wave-uniform)
         const int r = blk * 16 + lr;                         // tile row this lane fetches
-        int ar = min(r, nrows - 1);
-        if (rel) ar = rel[ar];                               // offsets from row0, below 2^32 bytes (checked on the host)
+        const int ar = a_row[i];
         a_voff[i] = (uint32_t)ar * (uint32_t)lda * 2u + (uint32_t)lc * 16u;
         int col;
         if (EPI == EPI_SWIGLU) {
